@@ -1,0 +1,207 @@
+"""ctypes binding of the CPU oracle (oracle/fpq_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the benchmark's
+CPU-baseline leg.  Nothing on the product path may import this package, and this package
+imports nothing from the GPU library.
+
+A format is a tuple (e, m, b, c): exponent bits, mantissa bits, integer bias, maximum
+magnitude (Section IV-B, Eq. (5)-(7)).  Codes are numpy uint8, one code per element.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        L = C.CDLL(path)
+        L.oracle_format_max.restype = C.c_double
+        L.oracle_format_max.argtypes = [C.c_int] * 3
+        L.oracle_decode.restype = C.c_double
+        L.oracle_decode.argtypes = [C.c_int, C.c_int, C.c_int, C.c_uint]
+        L.oracle_quantize_one.restype = C.c_uint
+        L.oracle_quantize_one.argtypes = [C.c_float, C.c_int, C.c_int, C.c_int, C.c_double, C.c_float]
+        L.oracle_quantize_mask_one.restype = C.c_uint
+        L.oracle_quantize_mask_one.argtypes = [C.c_float, C.c_uint, C.c_int, C.c_int, C.c_int,
+                                               C.c_double, C.c_float]
+        L.oracle_quantize.restype = None
+        L.oracle_quantize.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_int, C.c_double,
+                                      C.c_float, C.c_void_p]
+        L.oracle_quantize_mask.restype = None
+        L.oracle_quantize_mask.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_int,
+                                           C.c_int, C.c_double, C.c_float, C.c_void_p]
+        L.oracle_absmax.restype = C.c_float
+        L.oracle_absmax.argtypes = [C.c_void_p, C.c_size_t]
+        L.oracle_scale_from_absmax.restype = C.c_float
+        L.oracle_scale_from_absmax.argtypes = [C.c_float, C.c_double]
+        L.oracle_pack_weights.restype = None
+        L.oracle_pack_weights.argtypes = [C.c_void_p, C.c_void_p, C.c_long, C.c_long, C.c_int, C.c_int,
+                                          C.c_int, C.c_double, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.oracle_pack4.restype = None
+        L.oracle_pack4.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
+        L.oracle_dequantize.restype = None
+        L.oracle_dequantize.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_int, C.c_double,
+                                        C.c_void_p]
+        L.oracle_gemm.restype = None
+        L.oracle_gemm.argtypes = ([C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_float,
+                                   C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                   C.c_long, C.c_long, C.c_long, C.c_void_p, C.c_long,
+                                   C.c_void_p, C.c_void_p])
+        L.oracle_conv2d.restype = None
+        L.oracle_conv2d.argtypes = ([C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_float,
+                                     C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+                                    + [C.c_long] * 9 + [C.c_void_p, C.c_long, C.c_void_p, C.c_void_p])
+        L.oracle_num_threads.restype = C.c_int
+        L.oracle_num_threads.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _u8(a):
+    return np.ascontiguousarray(a, dtype=np.uint8)
+
+
+def format_max(e, m, b):
+    """Eq. (7)."""
+    return lib().oracle_format_max(e, m, b)
+
+
+def decode(fmt, code):
+    e, m, b, _ = fmt
+    return lib().oracle_decode(e, m, b, int(code))
+
+
+def grid(fmt):
+    """All non-negative magnitudes of the format, indexed by code (sign bit clear)."""
+    e, m, b, _ = fmt
+    return np.array([lib().oracle_decode(e, m, b, k) for k in range(1 << (e + m))])
+
+
+def quantize_one(x, fmt, scale=1.0):
+    e, m, b, c = fmt
+    return lib().oracle_quantize_one(float(np.float32(x)), e, m, b, float(c), float(np.float32(scale)))
+
+
+def quantize_mask_one(w, h, fmt, scale=1.0):
+    e, m, b, c = fmt
+    return lib().oracle_quantize_mask_one(float(np.float32(w)), int(h), e, m, b, float(c),
+                                          float(np.float32(scale)))
+
+
+def quantize(x, fmt, scale=1.0):
+    """Eq. (6), (8), (9): nearest-value codes of x / scale, same shape as x."""
+    e, m, b, c = fmt
+    x = _f32(x)
+    out = np.empty(x.shape, dtype=np.uint8)
+    lib().oracle_quantize(_p(x), x.size, e, m, b, float(c), float(np.float32(scale)), _p(out))
+    return out
+
+
+def quantize_mask(w, h, fmt, scale=1.0):
+    """Eq. (12) with a fixed 0/1 mask h."""
+    e, m, b, c = fmt
+    w = _f32(w)
+    h = _u8(h)
+    assert h.shape == w.shape
+    out = np.empty(w.shape, dtype=np.uint8)
+    lib().oracle_quantize_mask(_p(w), _p(h), w.size, e, m, b, float(c), float(np.float32(scale)), _p(out))
+    return out
+
+
+def absmax(x):
+    x = _f32(x)
+    return float(lib().oracle_absmax(_p(x), x.size))
+
+
+def scale_from_absmax(a, c):
+    return float(lib().oracle_scale_from_absmax(float(np.float32(a)), float(c)))
+
+
+def pack_weights(w, fmt, h=None, scale=None):
+    """Per-output-channel weight quantization of w[N, ...]; returns (codes, scale[N])."""
+    e, m, b, c = fmt
+    w = _f32(w)
+    N = w.shape[0]
+    K = w.size // N
+    hh = None if h is None else _u8(h)
+    sc_in = None if scale is None else _f32(scale)
+    sc_out = np.empty(N, dtype=np.float32)
+    codes = np.empty(w.shape, dtype=np.uint8)
+    lib().oracle_pack_weights(_p(w), _p(hh), N, K, e, m, b, float(c), _p(sc_in), _p(sc_out), _p(codes))
+    return codes, sc_out
+
+
+def pack4(codes):
+    codes = _u8(codes).reshape(-1)
+    out = np.empty((codes.size + 1) // 2, dtype=np.uint8)
+    lib().oracle_pack4(_p(codes), codes.size, _p(out))
+    return out
+
+
+def dequantize(codes, fmt, scale=1.0):
+    e, m, b, _ = fmt
+    codes = _u8(codes)
+    out = np.empty(codes.shape, dtype=np.float64)
+    lib().oracle_dequantize(_p(codes), codes.size, e, m, b, float(scale), _p(out))
+    return out
+
+
+def gemm(xq, fx, sx, wq, fw, sw, bias=None, rows=None):
+    """Quantized linear layer on codes: returns (Y, T) as float64 [M or len(rows), N]."""
+    xq = _u8(xq)
+    wq = _u8(wq)
+    M, K = xq.shape
+    N, K2 = wq.shape
+    assert K == K2
+    sw = _f32(sw)
+    assert sw.shape == (N,)
+    bias_ = None if bias is None else _f32(bias)
+    rows_ = None if rows is None else np.ascontiguousarray(rows, dtype=np.int64)
+    R = M if rows_ is None else rows_.size
+    Y = np.empty((R, N), dtype=np.float64)
+    T = np.empty((R, N), dtype=np.float64)
+    lib().oracle_gemm(_p(xq), fx[0], fx[1], fx[2], float(np.float32(sx)),
+                      _p(wq), fw[0], fw[1], fw[2], _p(sw), _p(bias_),
+                      M, N, K, _p(rows_), R, _p(Y), _p(T))
+    return Y, T
+
+
+def conv2d(xq, fx, sx, wq, fw, sw, bias=None, stride=1, pad=0, pix=None):
+    """Quantized conv2d on NCHW codes; returns (Y, T) NCHW float64, or [len(pix), Cout]."""
+    xq = _u8(xq)
+    wq = _u8(wq)
+    B, Cin, H, W = xq.shape
+    Cout, Cin2, kh, kw = wq.shape
+    assert Cin == Cin2
+    sw = _f32(sw)
+    bias_ = None if bias is None else _f32(bias)
+    Ho = (H + 2 * pad - kh) // stride + 1
+    Wo = (W + 2 * pad - kw) // stride + 1
+    pix_ = None if pix is None else np.ascontiguousarray(pix, dtype=np.int64)
+    shape = (B, Cout, Ho, Wo) if pix_ is None else (pix_.size, Cout)
+    Y = np.empty(shape, dtype=np.float64)
+    T = np.empty(shape, dtype=np.float64)
+    lib().oracle_conv2d(_p(xq), fx[0], fx[1], fx[2], float(np.float32(sx)),
+                        _p(wq), fw[0], fw[1], fw[2], _p(sw), _p(bias_),
+                        B, Cin, H, W, Cout, kh, kw, stride, pad,
+                        _p(pix_), 0 if pix_ is None else pix_.size, _p(Y), _p(T))
+    return Y, T
+
+
+def num_threads():
+    return lib().oracle_num_threads()

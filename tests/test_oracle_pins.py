@@ -1,0 +1,474 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU).
+
+Every check here is built without calling the oracle's own formulas a second time: grids are
+enumerated from Eq. (5) in Python, nearest values are found by brute force over that grid,
+native formats are compared with PyTorch's CPU float8 casts, uniform-grid formats with the
+textbook uniform quantizer, GEMM/conv with numpy / torch float64 routines on values decoded
+by the test's own Eq. (5).
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2408_06995_amd import synth
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+FORMATS_8 = [(e, 7 - e) for e in range(1, 6)]            # E1M6 .. E5M2
+FORMATS_4 = [(1, 2), (2, 1), (3, 0)]
+FORMATS_OTHER = [(2, 3), (3, 2), (3, 1), (4, 1), (2, 2), (4, 0), (1, 1)]
+ALL_EM = FORMATS_8 + FORMATS_4 + FORMATS_OTHER
+
+
+def biases_for(e):
+    return sorted({1 << (e - 1), (1 << (e - 1)) - 1, 1, 0, -2, 5})
+
+
+# ---------------------------------------------------------------- independent helpers
+
+def eq5_grid(e, m, b):
+    """Magnitudes indexed by code, from Eq. (5) for p >= 1 and the flat subnormal row for p = 0."""
+    g = []
+    for p in range(1 << e):
+        for f in range(1 << m):
+            if p == 0:
+                g.append(f * 2.0 ** (1 - b - m))
+            else:
+                g.append(2.0 ** (p - b) * (1 + sum(((f >> (m - i)) & 1) / 2.0 ** i for i in range(1, m + 1))))
+    return g
+
+
+def brute_nearest_code(y, e, m, b, c):
+    """argmin over the enumerated grid (<= c) of |clip(y) - g|; ties to the neighbour that is an
+    even multiple of the gap between the two candidates."""
+    g = [v for v in eq5_grid(e, m, b) if v <= c]
+    a = min(abs(y), c)
+    best = min(range(len(g)), key=lambda k: (abs(a - g[k]), k))
+    d = abs(a - g[best])
+    ties = [k for k in range(len(g)) if abs(a - g[k]) == d]
+    if len(ties) == 2:
+        lo, hi = ties
+        gap = g[hi] - g[lo]
+        best = lo if (g[lo] / gap) % 2 == 0 else hi
+    sign = 1 if math.copysign(1.0, y) < 0 else 0
+    return (sign << (e + m)) | best
+
+
+def dec(codes, e, m, b):
+    g = np.array(eq5_grid(e, m, b))
+    codes = np.asarray(codes).astype(np.int64)
+    mag = g[codes & ((1 << (e + m)) - 1)]
+    return np.where((codes >> (e + m)) & 1, -mag, mag)
+
+
+# ---------------------------------------------------------------- P1: Eq. (7)
+
+def test_format_max_closed_form_golden():
+    rows = [l.split() for l in open(os.path.join(GOLD, "format_max.txt")) if l.strip() and l[0] != "#"]
+    assert len(rows) >= 10
+    for e, m, b, c in rows:
+        e, m, b, c = int(e), int(m), int(b), float(c)
+        assert oracle.format_max(e, m, b) == c
+        assert max(eq5_grid(e, m, b)) == c           # all-ones code is the maximum
+        assert oracle.decode((e, m, b, c), (1 << (e + m)) - 1) == c
+
+
+@pytest.mark.parametrize("e,m", ALL_EM)
+def test_grid_structure(e, m):
+    for b in biases_for(e):
+        fmt = (e, m, b, oracle.format_max(e, m, b))
+        g = oracle.grid(fmt)
+        ref = np.array(eq5_grid(e, m, b))
+        assert g.shape == (1 << (e + m),)
+        assert np.array_equal(g, ref)                               # decode == Eq. (5)
+        assert np.all(np.diff(g) > 0)                               # strictly increasing in code
+        assert g[0] == 0.0
+        for a in range(1 - b, (1 << e) - b):                        # spacing 2^(a-m) in [2^a, 2^(a+1))
+            inside = g[(g >= 2.0 ** a) & (g < 2.0 ** (a + 1))]
+            assert len(inside) == 1 << m
+            if m:
+                assert np.all(np.diff(inside) == 2.0 ** (a - m))
+        sub = g[g < 2.0 ** (1 - b)]
+        assert len(sub) == 1 << m and (m == 0 or np.all(np.diff(sub) == 2.0 ** (1 - b - m)))
+        # sign bit
+        for code in (1, (1 << (e + m)) - 1):
+            assert oracle.decode(fmt, code | (1 << (e + m))) == -g[code]
+
+
+def test_e2m1_value_set_golden():
+    vals = [float(v) for l in open(os.path.join(GOLD, "e2m1_values.txt")) if l[0] != "#" for v in l.split()]
+    assert list(oracle.grid(synth.E2M1)) == vals
+    assert list(oracle.grid(synth.E1M2)) == [0.25 * k for k in range(8)]
+
+
+# ---------------------------------------------------------------- P3: uniform special case
+
+def test_e1m2_equals_textbook_uniform_quantizer():
+    """E1M2 (bias 1) is the uniform grid 0.25*k, |k| <= 7, so Eq. (6)-(9) must reduce to the symmetric
+    uniform quantizer 0.25*clamp(rne(x/0.25), -7, 7) (Eq. (4) with zero point 0)."""
+    rng = np.random.default_rng(3)
+    x = np.concatenate([rng.normal(0, 1, 200000), rng.uniform(-2.5, 2.5, 200000),
+                        0.125 * np.arange(-20, 21)]).astype(np.float32)
+    codes = oracle.quantize(x, synth.E1M2, 1.0)
+    got = dec(codes, 1, 2, 1)
+    want = 0.25 * np.clip(np.rint(x.astype(np.float64) / 0.25), -7, 7)
+    assert np.array_equal(got, want)
+
+
+# ---------------------------------------------------------------- P4: library casts
+
+def _edge_inputs_f32():
+    rng = np.random.default_rng(11)
+    bits = np.concatenate([
+        np.arange(0, 2 ** 32, 40961, dtype=np.uint64),                       # strided sweep of all patterns
+        rng.integers(0, 2 ** 32, 400000, dtype=np.uint64),
+    ]).astype(np.uint32)
+    x = bits.view(np.float32)
+    x = x[~np.isnan(x)]
+    # every fp32 neighbourhood of small powers of two and of multiples of 2^-10 near them
+    base = np.array([s * 2.0 ** k * (1 + j / 16.0) for k in range(-20, 18) for j in range(0, 32)
+                     for s in (1, -1)], dtype=np.float32)
+    nb = np.concatenate([base, np.nextafter(base, np.float32(np.inf)), np.nextafter(base, np.float32(-np.inf))])
+    return np.concatenate([x, nb, np.array([0.0, -0.0, np.inf, -np.inf], dtype=np.float32)])
+
+
+@pytest.mark.parametrize("fmt,tdtype", [(synth.E4M3, torch.float8_e4m3fn), (synth.E5M2, torch.float8_e5m2)])
+def test_native_formats_equal_torch_cpu_float8_cast(fmt, tdtype):
+    """With c = the hardware maximum and scale 1, the codes after the Eq. (6) clamp are the bytes of
+    PyTorch's CPU cast to the OCP float8 type (round-to-nearest-even, subnormals, signed zero)."""
+    x = _edge_inputs_f32()
+    c = np.float32(fmt[3])
+    codes = oracle.quantize(x, fmt, 1.0)
+    want = torch.from_numpy(np.clip(x, -c, c)).to(tdtype).view(torch.uint8).numpy()
+    assert np.array_equal(codes, want)
+    # decode equals the cast back
+    back = torch.from_numpy(codes.copy()).view(tdtype).to(torch.float64).numpy()
+    assert np.array_equal(oracle.dequantize(codes, fmt, 1.0), back)
+
+
+# ---------------------------------------------------------------- P5: exhaustive enumeration
+
+@pytest.mark.parametrize("e,m", ALL_EM)
+def test_idempotence_midpoints_and_neighbours(e, m):
+    for b in biases_for(e):
+        cmax = oracle.format_max(e, m, b)
+        g_all = eq5_grid(e, m, b)
+        for c in {cmax, g_all[-2], g_all[len(g_all) // 2]}:
+            if c <= 0:
+                continue
+            fmt = (e, m, b, c)
+            g = [v for v in g_all if v <= c]
+            for code, v in enumerate(g):
+                for sgn in (0, 1):
+                    x = -v if sgn else v
+                    assert oracle.quantize_one(x, fmt) == (sgn << (e + m)) | code
+            for k in range(len(g) - 1):
+                lo, hi = g[k], g[k + 1]
+                mid = 0.5 * (lo + hi)
+                assert float(np.float32(mid)) == mid
+                gap = hi - lo
+                even = k if (lo / gap) % 2 == 0 else k + 1
+                assert oracle.quantize_one(mid, fmt) == even
+                assert oracle.quantize_one(-mid, fmt) == even | (1 << (e + m))
+                below = float(np.nextafter(np.float32(mid), np.float32(-np.inf)))
+                above = float(np.nextafter(np.float32(mid), np.float32(np.inf)))
+                assert oracle.quantize_one(below, fmt) == k
+                assert oracle.quantize_one(above, fmt) == k + 1
+            # clipping to the max value
+            for x in (c * 1.0001, c * 3, 1e30, float("inf")):
+                assert oracle.quantize_one(x, fmt) == len(g) - 1
+                assert oracle.quantize_one(-x, fmt) == (len(g) - 1) | (1 << (e + m))
+
+
+# ---------------------------------------------------------------- P6: brute-force nearest
+
+@pytest.mark.parametrize("e,m,b", [(4, 3, 7), (5, 2, 15), (2, 1, 1), (1, 2, 1), (3, 4, 4), (2, 5, 2),
+                                     (3, 0, 4), (4, 3, 9), (3, 2, 0), (2, 3, -2)])
+def test_formula_equals_brute_force_nearest(e, m, b):
+    cmax = oracle.format_max(e, m, b)
+    g = eq5_grid(e, m, b)
+    rng = np.random.default_rng(e * 100 + m * 10 + b + 50)
+    for c in (cmax, g[-2]):
+        fmt = (e, m, b, c)
+        x = np.concatenate([
+            rng.normal(0, c / 3, 3000), rng.uniform(-1.2 * c, 1.2 * c, 3000),
+            rng.normal(0, g[1] * 4 if len(g) > 1 else 1, 2000),
+            np.array([s * v for v in g for s in (1, -1)]),
+        ]).astype(np.float32)
+        edges = np.array([2.0 ** a for a in range(-b - m - 2, (1 << e) - b + 1)], dtype=np.float32)
+        x = np.concatenate([x, edges, np.nextafter(edges, np.float32(0)), np.nextafter(edges, np.float32(np.inf)),
+                            -edges])
+        codes = oracle.quantize(x, fmt, 1.0)
+        for xi, ci in zip(x.tolist(), codes.tolist()):
+            assert ci == brute_nearest_code(xi, e, m, b, c), (xi, fmt)
+
+
+def test_formula_equals_brute_force_with_scale():
+    """y = fl32(x * fl32(1/scale)) then nearest on the grid."""
+    rng = np.random.default_rng(77)
+    for fmt in (synth.E4M3, synth.E2M1, synth.E3M4):
+        e, m, b, c = fmt
+        for scale in (np.float32(0.0371), np.float32(3.3), np.float32(2.0 ** -5)):
+            x = rng.normal(0, 3 * scale * c / 4, 4000).astype(np.float32)
+            codes = oracle.quantize(x, fmt, scale)
+            r = np.float32(1.0) / scale
+            y = (x * r).astype(np.float32)
+            for xi, yi, ci in zip(x.tolist(), y.tolist(), codes.tolist()):
+                assert ci == brute_nearest_code(yi if yi != 0 else math.copysign(0.0, xi), e, m, b, c)
+
+
+# ---------------------------------------------------------------- P7: invariants
+
+@pytest.mark.parametrize("fmt", [synth.E4M3, synth.E5M2, synth.E2M1, synth.E1M2, synth.E3M4, synth.E2M5,
+                                  synth.E3M0, (4, 3, 7, 480.0)])
+def test_invariants(fmt):
+    e, m, b, c = fmt
+    rng = np.random.default_rng(5)
+    scale = np.float32(0.173)
+    x = np.sort(np.concatenate([rng.normal(0, c * scale / 2, 100000), rng.uniform(-2 * c * scale, 2 * c * scale, 50000)]
+                               ).astype(np.float32))
+    codes = oracle.quantize(x, fmt, scale)
+    q = dec(codes, e, m, b)
+    assert np.all(np.diff(q) >= 0)                                            # monotone
+    assert np.all(np.abs(q) <= c)                                             # never above c
+    codes_neg = oracle.quantize(-x, fmt, scale)
+    assert np.array_equal(codes_neg, codes ^ (1 << (e + m)))                  # odd symmetry
+    y = (x * (np.float32(1) / scale)).astype(np.float32).astype(np.float64)
+    yc = np.clip(y, -c, c)
+    a = np.abs(yc)
+    E = np.floor(np.log2(np.where(a > 0, a, 1.0)))
+    # recompute floor(log2) exactly by correcting with comparisons
+    E = np.where(2.0 ** E > a, E - 1, E)
+    E = np.where(2.0 ** (E + 1) <= a, E + 1, E)
+    s = 2.0 ** (np.maximum(E + b, 1) - b - m)
+    s = np.where(a == 0, 2.0 ** (1 - b - m), s)
+    assert np.all(np.abs(yc - q) <= s / 2)                                    # within half a step
+    big = np.abs(y) >= c
+    assert np.all(np.abs(q[big]) == c)                                        # clipping to the max value
+    # idempotence on the tensor level
+    again = oracle.quantize(q.astype(np.float32), fmt, 1.0)
+    assert np.array_equal(dec(again, e, m, b), q)
+
+
+# ---------------------------------------------------------------- P9: bias <-> scale
+
+def test_power_of_two_scale_equals_bias_shift():
+    rng = np.random.default_rng(9)
+    x = rng.normal(0, 1, 50000).astype(np.float32)
+    for (e, m, b, c) in (synth.E4M3, synth.E2M1, synth.E3M4):
+        for j in (-3, 2, 5):
+            a = oracle.quantize(x, (e, m, b, c), np.float32(2.0 ** j))
+            bb = oracle.quantize(x, (e, m, b - j, c * 2.0 ** j), 1.0)
+            assert np.array_equal(a, bb)
+
+
+# ---------------------------------------------------------------- P10: Eq. (12) mask quantizer
+
+@pytest.mark.parametrize("fmt", [synth.E2M1, synth.E1M2, synth.E4M3, synth.E3M4, synth.E3M0, (2, 1, 2, 3.0)])
+def test_mask_quantizer_floor_ceil_on_grid(fmt):
+    e, m, b, c = fmt
+    g = np.array([v for v in eq5_grid(e, m, b) if v <= c])
+    full = np.concatenate([-g[::-1], g[1:]])                     # signed grid, increasing
+    rng = np.random.default_rng(21)
+    scale = np.float32(0.031)
+    w = np.concatenate([rng.normal(0, c * scale / 2.5, 40000), rng.uniform(-1.3 * c * scale, 1.3 * c * scale, 10000)]
+                       ).astype(np.float32)
+    y = (w * (np.float32(1) / scale)).astype(np.float32).astype(np.float64)
+    yc = np.clip(y, -c, c)
+    on_grid = np.isin(yc, full)
+    c0 = oracle.quantize_mask(w, np.zeros_like(w, dtype=np.uint8), fmt, scale)
+    c1 = oracle.quantize_mask(w, np.ones_like(w, dtype=np.uint8), fmt, scale)
+    q0, q1 = dec(c0, e, m, b), dec(c1, e, m, b)
+    idx = np.searchsorted(full, yc, side="right")                # full[idx-1] <= yc < full[idx]
+    off = ~on_grid
+    assert off.sum() > 1000
+    assert np.array_equal(q0[off], full[idx[off] - 1])           # h = 0: grid floor
+    assert np.array_equal(q1[off], full[idx[off]])               # h = 1: grid ceil
+    # nearest is one of the two, and the mask "upper is nearest" reproduces Eq. (8)
+    cn = oracle.quantize(w, fmt, scale)
+    qn = dec(cn, e, m, b)
+    assert np.all((qn[off] == q0[off]) | (qn[off] == q1[off]))
+    h_near = (qn == q1).astype(np.uint8)
+    h_near[on_grid] = 0
+    cm = oracle.quantize_mask(w, h_near, fmt, scale)
+    assert np.array_equal(dec(cm, e, m, b), qn)
+    assert np.array_equal(cm[qn != 0], cn[qn != 0])
+    # on-grid inputs follow Eq. (12) literally: h = 0 keeps the value, h = 1 adds one step, then clamp
+    assert np.array_equal(q0[on_grid], yc[on_grid])
+    for v in g:
+        for sgn in (1.0, -1.0):
+            wv = sgn * v
+            assert dec([oracle.quantize_mask_one(wv, 0, fmt)], e, m, b)[0] == wv
+            a = abs(wv)
+            E = math.floor(math.log2(a)) if a > 0 else -10 ** 6
+            step = 2.0 ** (max(E + b, 1) - b - m)
+            want = min(wv + step, c)
+            assert dec([oracle.quantize_mask_one(wv, 1, fmt)], e, m, b)[0] == want
+    # codes are always valid (encodable, |q| <= c)
+    assert np.all(np.abs(q0) <= c) and np.all(np.abs(q1) <= c)
+    assert np.all(c0 < (1 << (1 + e + m))) and np.all(c1 < (1 << (1 + e + m)))
+
+
+def test_mask_sign_of_zero_and_floor_direction():
+    fmt = synth.E2M1
+    # -0.2 lies between -0.5 and 0: floor is towards minus infinity
+    assert oracle.quantize_mask_one(-0.2, 0, fmt) == 0b1001          # -0.5
+    assert oracle.quantize_mask_one(-0.2, 1, fmt) == 0b1000          # -0 keeps the input's sign
+    assert oracle.quantize_mask_one(0.2, 0, fmt) == 0b0000
+    assert oracle.quantize_mask_one(0.2, 1, fmt) == 0b0001
+    assert oracle.quantize_mask_one(7.0, 1, fmt) == 0b0111           # clamp at +c
+    assert oracle.quantize_mask_one(-7.0, 0, fmt) == 0b1111
+    assert oracle.quantize_mask_one(-7.0, 1, fmt) == 0b1110          # -6 + 2 = -4
+
+
+# ---------------------------------------------------------------- per-channel scale, packing
+
+def test_pack_weights_scale_and_nibbles():
+    w = synth.weights((12, 40), 4500)
+    h = synth.rounding_mask((12, 40), 4750)
+    codes, sw = oracle.pack_weights(w, synth.E2M1, h)
+    want_s = (np.abs(w).max(axis=1) / np.float32(6.0)).astype(np.float32)
+    assert np.array_equal(sw, want_s)
+    for n in range(12):
+        assert np.array_equal(codes[n], oracle.quantize_mask(w[n], h[n], synth.E2M1, sw[n]))
+    codes_n, _ = oracle.pack_weights(w, synth.E2M1)
+    assert np.all(np.abs(dec(codes_n, 2, 1, 1)).max(axis=1) == 6.0)      # absmax maps to c
+    p = oracle.pack4(codes.reshape(-1))
+    flat = codes.reshape(-1)
+    assert np.array_equal(p & 0xF, flat[0::2]) and np.array_equal(p >> 4, flat[1::2])
+    z, sz = oracle.pack_weights(np.zeros((2, 8), np.float32), synth.E4M3)
+    assert np.all(sz == 1.0) and np.all(z == 0)
+
+
+# ---------------------------------------------------------------- P11/P12/P14: GEMM
+
+def test_gemm_tiny_brute_force():
+    rng = np.random.default_rng(1)
+    fx, fw = synth.E4M3, synth.E2M1
+    for M, N, K in [(1, 1, 1), (2, 3, 5), (4, 4, 16), (3, 2, 7)]:
+        xq = rng.integers(0, 256, (M, K), dtype=np.uint8)
+        xq[(xq & 0x7F) == 0x7F] = 0x7E
+        wq = rng.integers(0, 16, (N, K), dtype=np.uint8)
+        sw = rng.uniform(0.01, 0.1, N).astype(np.float32)
+        bias = rng.normal(0, 1, N).astype(np.float32)
+        sx = np.float32(0.37)
+        Y, T = oracle.gemm(xq, fx, sx, wq, fw, sw, bias)
+        gx, gw = eq5_grid(4, 3, 7), eq5_grid(2, 1, 1)
+        for i, j in itertools.product(range(M), range(N)):
+            acc = 0.0
+            accabs = 0.0
+            for k in range(K):
+                a = gx[xq[i, k] & 0x7F] * (-1 if xq[i, k] & 0x80 else 1)
+                bb = gw[wq[j, k] & 0x7] * (-1 if wq[j, k] & 0x8 else 1)
+                acc += a * bb
+                accabs += abs(a * bb)
+            assert Y[i, j] == float(sx) * float(sw[j]) * acc + float(bias[j])
+            assert T[i, j] == float(sx) * float(sw[j]) * accabs
+
+
+def test_gemm_equals_numpy_matmul_of_decoded_values():
+    rng = np.random.default_rng(2)
+    M, N, K = 37, 29, 200
+    for fx, fw in [(synth.E4M3, synth.E4M3), (synth.E4M3, synth.E2M1), (synth.E3M4, synth.E3M0)]:
+        x = synth.activations((M, K), 17)
+        w = synth.weights((N, K), 18)
+        sx = oracle.scale_from_absmax(oracle.absmax(x), fx[3])
+        xq = oracle.quantize(x, fx, sx)
+        wq, sw = oracle.pack_weights(w, fw, synth.rounding_mask((N, K), 19))
+        Y, T = oracle.gemm(xq, fx, sx, wq, fw, sw)
+        A = dec(xq, *fx[:3])
+        Bm = dec(wq, *fw[:3])
+        ref = (A @ Bm.T) * (float(np.float32(sx)) * sw.astype(np.float64))[None, :]
+        assert np.allclose(Y, ref, rtol=1e-12, atol=1e-15)
+        refT = (np.abs(A) @ np.abs(Bm).T) * (float(np.float32(sx)) * sw.astype(np.float64))[None, :]
+        assert np.allclose(T, refT, rtol=1e-12)
+        # the quantized layer approximates the full-precision one (sanity of scale handling)
+        full = x.astype(np.float64) @ w.astype(np.float64).T
+        assert np.abs(Y - full).mean() < (0.12 if fw[0] + fw[1] > 3 else 0.5) * np.abs(full).mean()
+        # rows subset
+        rows = np.array([5, 0, 36])
+        Ys, Ts = oracle.gemm(xq, fx, sx, wq, fw, sw, rows=rows)
+        assert np.array_equal(Ys, Y[rows]) and np.array_equal(Ts, T[rows])
+        # P14: scale linearity
+        Y2, _ = oracle.gemm(xq, fx, 2 * sx, wq, fw, sw)
+        assert np.array_equal(Y2, 2 * Y)
+
+
+def test_gemm_exact_integer_case():
+    rng = np.random.default_rng(4)
+    M, N, K = 16, 8, 64
+    vals = np.array([0, 1, 2, 3, 4, -1, -2, -3, -4, 6, -6, 8], dtype=np.float32)
+    x = rng.choice(vals, (M, K))
+    w = rng.choice(np.array([0, 1, 2, 3, 4, 6, -1, -2, -3, -4, -6], dtype=np.float32), (N, K))
+    xq = oracle.quantize(x, synth.E4M3, 1.0)
+    wq = oracle.quantize(w, synth.E2M1, 1.0)
+    Y, _ = oracle.gemm(xq, synth.E4M3, 1.0, wq, synth.E2M1, np.ones(N, np.float32))
+    assert np.array_equal(Y, x.astype(np.float64) @ w.astype(np.float64).T)
+
+
+# ---------------------------------------------------------------- P13: conv
+
+@pytest.mark.parametrize("k,stride,pad", [(3, 1, 1), (1, 1, 0), (3, 2, 1), (3, 1, 0)])
+def test_conv_equals_torch_float64_conv_and_im2col(k, stride, pad):
+    fx, fw = synth.E4M3, synth.E2M1
+    B, Cin, H, W, Cout = 2, 5, 7, 6, 4
+    x = synth.activations((B, Cin, H, W), 31)
+    w = synth.weights((Cout, Cin, k, k), 32)
+    sx = oracle.scale_from_absmax(oracle.absmax(x), fx[3])
+    xq = oracle.quantize(x, fx, sx)
+    wq, sw = oracle.pack_weights(w, fw, synth.rounding_mask(w.shape, 33))
+    bias = np.linspace(-1, 1, Cout).astype(np.float32)
+    Y, T = oracle.conv2d(xq, fx, sx, wq, fw, sw, bias, stride=stride, pad=pad)
+    A = torch.from_numpy(dec(xq, *fx[:3]))
+    Wd = torch.from_numpy(dec(wq, *fw[:3]))
+    ref = torch.nn.functional.conv2d(A, Wd, None, stride=stride, padding=pad).numpy()
+    ref = ref * (float(np.float32(sx)) * sw.astype(np.float64))[None, :, None, None] + bias[None, :, None, None]
+    assert Y.shape == ref.shape
+    assert np.allclose(Y, ref, rtol=1e-12, atol=1e-14)
+    refT = torch.nn.functional.conv2d(A.abs(), Wd.abs(), None, stride=stride, padding=pad).numpy()
+    refT = refT * (float(np.float32(sx)) * sw.astype(np.float64))[None, :, None, None]
+    assert np.allclose(T, refT, rtol=1e-12)
+    # conv == GEMM over an explicit im2col built here
+    Ho, Wo = Y.shape[2:]
+    xp = np.zeros((B, Cin, H + 2 * pad, W + 2 * pad), dtype=np.uint8)
+    xp[:, :, pad:pad + H, pad:pad + W] = xq
+    cols = np.zeros((B * Ho * Wo, Cin * k * k), dtype=np.uint8)
+    for bb, ho, wo in itertools.product(range(B), range(Ho), range(Wo)):
+        patch = xp[bb, :, ho * stride:ho * stride + k, wo * stride:wo * stride + k]
+        cols[(bb * Ho + ho) * Wo + wo] = patch.reshape(-1)
+    Yg, _ = oracle.gemm(cols, fx, sx, wq.reshape(Cout, -1), fw, sw, bias)
+    assert np.allclose(Yg.reshape(B, Ho, Wo, Cout).transpose(0, 3, 1, 2), Y, rtol=1e-12, atol=1e-14)
+    # pixel subset
+    pix = np.array([0, 3, B * Ho * Wo - 1])
+    Ys, _ = oracle.conv2d(xq, fx, sx, wq, fw, sw, bias, stride=stride, pad=pad, pix=pix)
+    full = Y.transpose(0, 2, 3, 1).reshape(-1, Cout)
+    assert np.array_equal(Ys, full[pix])
+
+
+def test_conv_one_hot_taps():
+    """A single 1 in the input and a single 1 in the weight locate every (ci, kh, kw) tap and the border."""
+    one = oracle.quantize_one(1.0, synth.E4M3)
+    B, Cin, H, W, Cout, k = 1, 2, 4, 5, 2, 3
+    for ci, r, t, hi, wi in [(0, 0, 0, 0, 0), (1, 2, 1, 3, 4), (0, 1, 2, 2, 0), (1, 0, 2, 0, 4)]:
+        xq = np.zeros((B, Cin, H, W), np.uint8)
+        wq = np.zeros((Cout, Cin, k, k), np.uint8)
+        xq[0, ci, hi, wi] = one
+        wq[1, ci, r, t] = one
+        Y, _ = oracle.conv2d(xq, synth.E4M3, 1.0, wq, synth.E4M3, np.ones(Cout, np.float32), stride=1, pad=1)
+        want = np.zeros((B, Cout, H, W))
+        ho, wo = hi + 1 - r, wi + 1 - t
+        if 0 <= ho < H and 0 <= wo < W:
+            want[0, 1, ho, wo] = 1.0
+        assert np.array_equal(Y, want)
+
+
+def test_absmax_and_scale():
+    x = synth.activations((1000,), 1)
+    assert oracle.absmax(x) == float(np.abs(x).max())
+    assert oracle.scale_from_absmax(10.0, 448.0) == float(np.float32(10.0) / np.float32(448.0))
+    assert oracle.scale_from_absmax(0.0, 448.0) == 1.0
