@@ -1,0 +1,189 @@
+"""Thin ctypes binding of libfpq.so: same names as the C ABI (include/fpq.h), argument marshalling only.
+
+Tensors are torch tensors on the GPU (PyTorch supplies device memory and streams, nothing else);
+every function below forwards their data pointers to the C entry point of the same name on the
+current torch stream and raises FpqError on a non-zero status.  There is no CPU fallback: if the
+shared library is missing or does not load, importing the functions' library handle fails.
+"""
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libfpq.so")
+
+FPQ_ACC_FP32 = 0
+FPQ_ACC_FP8_MFMA = 1
+
+
+class fpq_format_t(C.Structure):
+    _fields_ = [("ebits", C.c_int32), ("mbits", C.c_int32), ("bias", C.c_int32), ("maxval", C.c_float)]
+
+
+class FpqError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib().fpq_strerror(status).decode()
+        super().__init__("%s: status %d (%s)" % (where, status, msg))
+
+
+_lib = None
+
+
+def lib():
+    """Load libfpq.so (built by paper_2408_06995_amd.build); loud failure if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libfpq.so not built: run `python -m paper_2408_06995_amd.build` (%s)" % LIB_PATH)
+    L = C.CDLL(LIB_PATH)
+    vp, f32p, u8p, sz, i64, i32, fl = C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_int64, C.c_int, C.c_float
+    F = fpq_format_t
+    L.fpq_strerror.restype = C.c_char_p
+    L.fpq_strerror.argtypes = [i32]
+    L.fpq_format_max.restype = fl
+    L.fpq_format_max.argtypes = [i32, i32, i32]
+    L.fpq_format_check.restype = i32
+    L.fpq_format_check.argtypes = [F]
+    L.fpq_bias_to_scale.restype = i32
+    L.fpq_bias_to_scale.argtypes = [i32, i32, C.c_double, C.POINTER(C.c_int32), C.POINTER(C.c_float)]
+    L.fpq_code_bytes.restype = sz
+    L.fpq_code_bytes.argtypes = [sz, F]
+    L.fpq_absmax_workspace_size.restype = sz
+    L.fpq_absmax_workspace_size.argtypes = [sz]
+    L.fpq_absmax.restype = i32
+    L.fpq_absmax.argtypes = [f32p, sz, fl, f32p, f32p, vp, sz, vp]
+    L.fpq_quantize.restype = i32
+    L.fpq_quantize.argtypes = [f32p, sz, F, fl, f32p, u8p, vp]
+    L.fpq_padded_channels.restype = i64
+    L.fpq_padded_channels.argtypes = [i64]
+    L.fpq_quantize_nhwc.restype = i32
+    L.fpq_quantize_nhwc.argtypes = [f32p, i64, i64, i64, i64, F, fl, f32p, u8p, vp]
+    L.fpq_dequantize.restype = i32
+    L.fpq_dequantize.argtypes = [u8p, sz, F, fl, f32p, vp]
+    L.fpq_packed_size.restype = sz
+    L.fpq_packed_size.argtypes = [i64, i64, i32, i32, F]
+    L.fpq_pack_weights.restype = i32
+    L.fpq_pack_weights.argtypes = [f32p, i64, i64, i32, i32, F, f32p, u8p, vp, sz, f32p, u8p, vp]
+    L.fpq_gemm_workspace_size.restype = sz
+    L.fpq_gemm_workspace_size.argtypes = [i64, i64, i64, i32]
+    L.fpq_gemm.restype = i32
+    L.fpq_gemm.argtypes = [vp, i32, F, fl, f32p, vp, F, f32p, f32p, f32p, i64, i64, i64, i32, vp, sz, vp]
+    L.fpq_conv2d_workspace_size.restype = sz
+    L.fpq_conv2d_workspace_size.argtypes = [i64, i64, i64, i64, i64, i32, i32, i32, i32, i32]
+    L.fpq_conv2d.restype = i32
+    L.fpq_conv2d.argtypes = ([vp, i32, F, fl, f32p, vp, F, f32p, f32p, f32p] + [i64] * 5 + [i32] * 5 + [vp, sz, vp])
+    _lib = L
+    return L
+
+
+EXPORTS = ["fpq_strerror", "fpq_format_max", "fpq_format_check", "fpq_bias_to_scale", "fpq_code_bytes",
+           "fpq_absmax_workspace_size", "fpq_absmax", "fpq_quantize", "fpq_padded_channels", "fpq_quantize_nhwc",
+           "fpq_dequantize", "fpq_packed_size", "fpq_pack_weights", "fpq_gemm_workspace_size", "fpq_gemm",
+           "fpq_conv2d_workspace_size", "fpq_conv2d"]
+
+
+def fmt(f):
+    """(e, m, b, c) tuple or fpq_format_t -> fpq_format_t."""
+    if isinstance(f, fpq_format_t):
+        return f
+    e, m, b, c = f
+    return fpq_format_t(int(e), int(m), int(b), float(c))
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status, where):
+    if status != 0:
+        raise FpqError(status, where)
+
+
+# ---- host helpers
+
+def fpq_format_max(e, m, b):
+    return lib().fpq_format_max(e, m, b)
+
+
+def fpq_format_check(f):
+    return lib().fpq_format_check(fmt(f))
+
+
+def fpq_bias_to_scale(e, m, real_bias):
+    ib, sc = C.c_int32(0), C.c_float(0)
+    _check(lib().fpq_bias_to_scale(e, m, float(real_bias), C.byref(ib), C.byref(sc)), "fpq_bias_to_scale")
+    return ib.value, sc.value
+
+
+def fpq_code_bytes(n, f):
+    return lib().fpq_code_bytes(n, fmt(f))
+
+
+def fpq_padded_channels(c):
+    return lib().fpq_padded_channels(c)
+
+
+def fpq_packed_size(N, Cin, kh, kw, f):
+    return lib().fpq_packed_size(N, Cin, kh, kw, fmt(f))
+
+
+def fpq_absmax_workspace_size(n):
+    return lib().fpq_absmax_workspace_size(n)
+
+
+def fpq_gemm_workspace_size(M, N, K, x_is_fp32):
+    return lib().fpq_gemm_workspace_size(M, N, K, int(x_is_fp32))
+
+
+def fpq_conv2d_workspace_size(B, Cin, H, W, Cout, kh, kw, stride, pad, x_is_fp32):
+    return lib().fpq_conv2d_workspace_size(B, Cin, H, W, Cout, kh, kw, stride, pad, int(x_is_fp32))
+
+
+# ---- device entry points (torch tensors in, status checked)
+
+def fpq_absmax(x, maxval, absmax_out, scale_out, workspace):
+    _check(lib().fpq_absmax(_ptr(x), x.numel(), float(maxval), _ptr(absmax_out), _ptr(scale_out), _ptr(workspace),
+                            workspace.numel() * workspace.element_size(), _stream()), "fpq_absmax")
+
+
+def fpq_quantize(x, f, scale, scale_dev, codes):
+    _check(lib().fpq_quantize(_ptr(x), x.numel(), fmt(f), float(scale), _ptr(scale_dev), _ptr(codes), _stream()),
+           "fpq_quantize")
+
+
+def fpq_quantize_nhwc(x, f, scale, scale_dev, codes):
+    B, Cc, H, W = x.shape
+    _check(lib().fpq_quantize_nhwc(_ptr(x), B, Cc, H, W, fmt(f), float(scale), _ptr(scale_dev), _ptr(codes), _stream()),
+           "fpq_quantize_nhwc")
+
+
+def fpq_dequantize(codes, f, scale, out):
+    _check(lib().fpq_dequantize(_ptr(codes), codes.numel(), fmt(f), float(scale), _ptr(out), _stream()), "fpq_dequantize")
+
+
+def fpq_pack_weights(w, f, scale, mask, packed, scale_out, codes_out=None):
+    N, Cin = w.shape[0], w.shape[1]
+    kh, kw = (w.shape[2], w.shape[3]) if w.dim() == 4 else (1, 1)
+    _check(lib().fpq_pack_weights(_ptr(w), N, Cin, kh, kw, fmt(f), _ptr(scale), _ptr(mask), _ptr(packed),
+                                  packed.numel() * packed.element_size(), _ptr(scale_out), _ptr(codes_out), _stream()),
+           "fpq_pack_weights")
+
+
+def fpq_gemm(x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, y, M, N, K, acc_mode=FPQ_ACC_FP32, workspace=None):
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().fpq_gemm(_ptr(x), int(x_is_fp32), fmt(fx), float(sx), _ptr(sx_dev), _ptr(packed_w), fmt(fw), _ptr(sw),
+                          _ptr(bias), _ptr(y), M, N, K, int(acc_mode), _ptr(workspace), wb, _stream()), "fpq_gemm")
+
+
+def fpq_conv2d(x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, y, B, Cin, H, W, Cout, kh, kw, stride, pad,
+               acc_mode=FPQ_ACC_FP32, workspace=None):
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().fpq_conv2d(_ptr(x), int(x_is_fp32), fmt(fx), float(sx), _ptr(sx_dev), _ptr(packed_w), fmt(fw), _ptr(sw),
+                            _ptr(bias), _ptr(y), B, Cin, H, W, Cout, kh, kw, stride, pad, int(acc_mode),
+                            _ptr(workspace), wb, _stream()), "fpq_conv2d")

@@ -1,0 +1,359 @@
+// C ABI of libfpq (see include/fpq.h): argument validation on the host, then kernel launches on
+// the caller's stream.  No entry point allocates, synchronizes or keeps a pointer.
+#include <math.h>
+#include <string.h>
+
+#include "fpq_dev.h"
+#include "fpq_host.h"
+
+using namespace fpq;
+
+namespace {
+
+bool em_ok(int e, int m, int b) { return e >= 1 && m >= 0 && 1 + e + m <= 8 && b >= -64 && b <= 64; }
+
+double eq7_max(int e, int m, int b) { return (2.0 - ldexp(1.0, -m)) * ldexp(1.0, (1 << e) - b - 1); }
+
+// Is v a magnitude of the (e, m, b) grid (Eq. (5) plus the subnormal row)?
+bool on_grid(int e, int m, int b, double v)
+{
+    if (!(v > 0.0) || v > eq7_max(e, m, b)) return false;
+    double lowest_normal = ldexp(1.0, 1 - b);
+    if (v < lowest_normal) {
+        double f = ldexp(v, -(1 - b - m));
+        return f == floor(f);
+    }
+    int ex;
+    double fr = frexp(v, &ex);
+    double f = ldexp(2.0 * fr - 1.0, m);
+    return f == floor(f);
+}
+
+// Validates f and fills the kernel parameters (maxval 0 -> Eq. (7)).
+int resolve_format(fpq_format_t f, QParams* q)
+{
+    if (!em_ok(f.ebits, f.mbits, f.bias)) return FPQ_ERR_FORMAT;
+    double c = f.maxval == 0.0f ? eq7_max(f.ebits, f.mbits, f.bias) : (double)f.maxval;
+    if (!(c == c) || !on_grid(f.ebits, f.mbits, f.bias, c)) return FPQ_ERR_FORMAT;
+    if (q) {
+        q->m = f.mbits;
+        q->b = f.bias;
+        q->em = f.ebits + f.mbits;
+        q->c = (float)c;
+    }
+    return FPQ_OK;
+}
+
+bool scale_ok(float s)
+{
+    if (!(s > 0.0f) || isinf(s)) return false;
+    float r = 1.0f / s;
+    return !isinf(r);
+}
+
+bool is_four_bit(fpq_format_t f) { return 1 + f.ebits + f.mbits <= 4; }
+
+// Which matrix-unit decoder reads this format's bit pattern, and the power of two between the
+// hardware's value of a code and the format's value (hardware biases: E4M3 7, E5M2 15, E2M1 1).
+// Hardware E4M3 has no value for the all-ones magnitude and hardware E5M2 none for the top
+// exponent, so a format whose maxval reaches those codes decodes arithmetically instead.
+int hardware_kind(fpq_format_t f, float c, bool weight, float* alpha)
+{
+    *alpha = 1.0f;
+    if (f.ebits == 4 && f.mbits == 3 && c <= 448.0 * ldexp(1.0, 7 - f.bias)) {
+        *alpha = (float)ldexp(1.0, 7 - f.bias);
+        return OPK_FP8;
+    }
+    if (f.ebits == 5 && f.mbits == 2 && c <= 57344.0 * ldexp(1.0, 15 - f.bias)) {
+        *alpha = (float)ldexp(1.0, 15 - f.bias);
+        return OPK_BF8;
+    }
+    if (weight && f.ebits == 2 && f.mbits == 1) {
+        *alpha = (float)ldexp(1.0, 1 - f.bias);
+        return OPK_FP4;
+    }
+    return (weight && is_four_bit(f)) ? OPK_GENERIC4 : OPK_GENERIC8;
+}
+
+// Operand kinds the kernels are instantiated for, and the epilogue factor alpha.
+int resolve_kinds(fpq_format_t fx, float cx, fpq_format_t fw, float cw, int acc_mode, int* xkind, int* wkind,
+                  float* alpha)
+{
+    float ax, aw;
+    int xk = hardware_kind(fx, cx, false, &ax);
+    int wk = hardware_kind(fw, cw, true, &aw);
+    if (is_four_bit(fx)) return FPQ_ERR_UNSUPPORTED;   // activations of <= 4 bits are not a case of the paper
+    if (acc_mode == FPQ_ACC_FP8_MFMA) {
+        if (xk == OPK_GENERIC8 || wk == OPK_GENERIC8 || wk == OPK_GENERIC4) return FPQ_ERR_UNSUPPORTED;
+    } else if (acc_mode == FPQ_ACC_FP32) {
+        if (!(xk == OPK_FP8 && (wk == OPK_FP8 || wk == OPK_FP4))) {
+            xk = OPK_GENERIC8;
+            wk = is_four_bit(fw) ? OPK_GENERIC4 : OPK_GENERIC8;
+            ax = aw = 1.0f;
+        }
+    } else {
+        return FPQ_ERR_UNSUPPORTED;
+    }
+    *xkind = xk;
+    *wkind = wk;
+    *alpha = ax * aw;
+    return FPQ_OK;
+}
+
+__global__ void write_header_kernel(PackedHeader h, uint32_t* dst)
+{
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(&h);
+    if (threadIdx.x < 16) dst[threadIdx.x] = src[threadIdx.x];
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace
+
+extern "C" {
+
+const char* fpq_strerror(int status)
+{
+    switch (status) {
+        case FPQ_OK: return "ok";
+        case FPQ_ERR_NULL: return "a required pointer is NULL";
+        case FPQ_ERR_FORMAT: return "invalid ExMy format (bits, bias, or maxval not on the grid)";
+        case FPQ_ERR_SCALE: return "scale must be positive and finite";
+        case FPQ_ERR_SHAPE: return "invalid or inconsistent sizes";
+        case FPQ_ERR_ALIGN: return "pointer or size not aligned as required";
+        case FPQ_ERR_WORKSPACE: return "workspace missing or too small";
+        case FPQ_ERR_LAUNCH: return "HIP launch failed";
+        case FPQ_ERR_UNSUPPORTED: return "no kernel for these arguments";
+        case FPQ_ERR_PACKED: return "packed weights do not match the arguments";
+        default: return "unknown status";
+    }
+}
+
+float fpq_format_max(int ebits, int mbits, int bias)
+{
+    if (!em_ok(ebits, mbits, bias)) return 0.0f;
+    return (float)eq7_max(ebits, mbits, bias);
+}
+
+int fpq_format_check(fpq_format_t f) { return resolve_format(f, nullptr); }
+
+int fpq_bias_to_scale(int ebits, int mbits, double real_bias, int32_t* int_bias, float* scale)
+{
+    if (!int_bias || !scale) return FPQ_ERR_NULL;
+    if (!(real_bias == real_bias) || isinf(real_bias)) return FPQ_ERR_FORMAT;
+    double fl = floor(real_bias);
+    if (!em_ok(ebits, mbits, (int)fl)) return FPQ_ERR_FORMAT;
+    *int_bias = (int32_t)fl;
+    *scale = (float)exp2(fl - real_bias);
+    return FPQ_OK;
+}
+
+size_t fpq_code_bytes(size_t n, fpq_format_t f) { return is_four_bit(f) ? (n + 1) / 2 : n; }
+
+size_t fpq_absmax_workspace_size(size_t n)
+{
+    int p = absmax_parts(n);
+    return (size_t)(p > 0 ? p : 1) * sizeof(float);
+}
+
+int fpq_absmax(const float* x, size_t n, float maxval, float* absmax_out, float* scale_out, void* workspace,
+               size_t workspace_bytes, void* stream)
+{
+    if (!absmax_out || !workspace || (n && !x)) return FPQ_ERR_NULL;
+    if (scale_out && !(maxval > 0.0f && !isinf(maxval))) return FPQ_ERR_FORMAT;
+    if (workspace_bytes < fpq_absmax_workspace_size(n)) return FPQ_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(x) & 3) || (reinterpret_cast<uintptr_t>(workspace) & 3)) return FPQ_ERR_ALIGN;
+    return launch_absmax(x, n, maxval, absmax_out, scale_out, static_cast<float*>(workspace),
+                         static_cast<hipStream_t>(stream));
+}
+
+int fpq_quantize(const float* x, size_t n, fpq_format_t f, float scale, const float* scale_dev, uint8_t* codes,
+                 void* stream)
+{
+    QParams q;
+    int st = resolve_format(f, &q);
+    if (st) return st;
+    if (!scale_dev && !scale_ok(scale)) return FPQ_ERR_SCALE;
+    if (n == 0) return FPQ_OK;
+    if (!x || !codes) return FPQ_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(x) & 3) return FPQ_ERR_ALIGN;
+    return launch_quantize(x, n, q, is_four_bit(f), scale, scale_dev, codes, static_cast<hipStream_t>(stream));
+}
+
+int64_t fpq_padded_channels(int64_t C) { return C > 0 ? padded_channels(C) : 0; }
+
+int fpq_quantize_nhwc(const float* x, int64_t B, int64_t C, int64_t H, int64_t W, fpq_format_t f, float scale,
+                      const float* scale_dev, uint8_t* codes, void* stream)
+{
+    QParams q;
+    int st = resolve_format(f, &q);
+    if (st) return st;
+    if (!scale_dev && !scale_ok(scale)) return FPQ_ERR_SCALE;
+    if (B <= 0 || C <= 0 || H <= 0 || W <= 0) return FPQ_ERR_SHAPE;
+    if (B > 65535 || H * W > (1 << 24) || B * H * W * padded_channels(C) >= (int64_t)1 << 31) return FPQ_ERR_SHAPE;
+    if (!x || !codes) return FPQ_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(x) & 3) || (reinterpret_cast<uintptr_t>(codes) & 15)) return FPQ_ERR_ALIGN;
+    return launch_quantize_nhwc(x, B, C, H, W, q, scale, scale_dev, codes, static_cast<hipStream_t>(stream));
+}
+
+int fpq_dequantize(const uint8_t* codes, size_t n, fpq_format_t f, float scale, float* out, void* stream)
+{
+    int st = resolve_format(f, nullptr);
+    if (st) return st;
+    if (!(scale == scale) || isinf(scale)) return FPQ_ERR_SCALE;
+    if (n == 0) return FPQ_OK;
+    if (!codes || !out) return FPQ_ERR_NULL;
+    return launch_dequantize(codes, n, f.ebits, f.mbits, f.bias, scale, out, static_cast<hipStream_t>(stream));
+}
+
+size_t fpq_packed_size(int64_t N, int64_t Cin, int kh, int kw, fpq_format_t f)
+{
+    if (N <= 0 || Cin <= 0 || kh <= 0 || kw <= 0 || resolve_format(f, nullptr)) return 0;
+    size_t kpad = (size_t)padded_k(Cin, (int64_t)kh * kw);
+    size_t row = is_four_bit(f) ? kpad / 2 : kpad;
+    return sizeof(PackedHeader) + (size_t)N * row;
+}
+
+int fpq_pack_weights(const float* w, int64_t N, int64_t Cin, int kh, int kw, fpq_format_t f, const float* scale,
+                     const uint8_t* mask, void* packed, size_t packed_bytes, float* scale_out, uint8_t* codes_out,
+                     void* stream)
+{
+    QParams q;
+    int st = resolve_format(f, &q);
+    if (st) return st;
+    if (N <= 0 || Cin <= 0 || kh <= 0 || kw <= 0 || kh > 64 || kw > 64) return FPQ_ERR_SHAPE;
+    if (N > 0x7fffffff || Cin * kh * kw > (1 << 28)) return FPQ_ERR_SHAPE;
+    if (!w || !packed || !scale_out) return FPQ_ERR_NULL;
+    if (packed_bytes < fpq_packed_size(N, Cin, kh, kw, f)) return FPQ_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(packed) & 15) || (reinterpret_cast<uintptr_t>(w) & 3)) return FPQ_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    PackedHeader h;
+    memset(&h, 0, sizeof h);
+    h.magic = kPackedMagic;
+    h.layout = 1;
+    h.ebits = f.ebits;
+    h.mbits = f.mbits;
+    h.bias = f.bias;
+    h.maxval = q.c;
+    h.N = N;
+    h.Cin = Cin;
+    h.kh = kh;
+    h.kw = kw;
+    h.Cp = (int32_t)padded_channels(Cin);
+    h.Kpad = (int32_t)padded_k(Cin, (int64_t)kh * kw);
+    hipLaunchKernelGGL(write_header_kernel, dim3(1), dim3(64), 0, s, h, static_cast<uint32_t*>(packed));
+    return launch_pack_weights(w, N, Cin, kh * kw, q, is_four_bit(f), scale, mask,
+                               static_cast<uint8_t*>(packed) + sizeof(PackedHeader), scale_out, codes_out, s);
+}
+
+size_t fpq_gemm_workspace_size(int64_t M, int64_t N, int64_t K, int x_is_fp32)
+{
+    (void)N;
+    if (M <= 0 || K <= 0 || !x_is_fp32) return 0;
+    return align_up((size_t)M * (size_t)padded_channels(K), 256);
+}
+
+size_t fpq_conv2d_workspace_size(int64_t B, int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh, int kw,
+                                 int stride, int pad, int x_is_fp32)
+{
+    (void)Cout; (void)kh; (void)kw; (void)stride; (void)pad;
+    if (B <= 0 || Cin <= 0 || H <= 0 || W <= 0 || !x_is_fp32) return 0;
+    return align_up((size_t)B * H * W * (size_t)padded_channels(Cin), 256);
+}
+
+static int run_layer(const void* x, int x_is_fp32, fpq_format_t fx, float sx, const float* sx_dev,
+                     const void* packed_w, fpq_format_t fw, const float* sw, const float* bias, float* y, int64_t B,
+                     int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh, int kw, int stride, int pad,
+                     int conv_out, int acc_mode, void* workspace, size_t workspace_bytes, void* stream)
+{
+    QParams qx, qw;
+    int st = resolve_format(fx, &qx);
+    if (st) return st;
+    st = resolve_format(fw, &qw);
+    if (st) return st;
+    if (!sx_dev && !scale_ok(sx)) return FPQ_ERR_SCALE;
+    if (B <= 0 || Cin <= 0 || H <= 0 || W <= 0 || Cout <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0)
+        return FPQ_ERR_SHAPE;
+    if (H + 2 * pad < kh || W + 2 * pad < kw || H > 16000 || W > 16000 || kh > 64 || kw > 64 || pad > 64)
+        return FPQ_ERR_SHAPE;
+    const int64_t Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
+    const int64_t M = B * Ho * Wo;
+    const int64_t Cp = padded_channels(Cin);
+    if (M >= (int64_t)1 << 31 || B * H * W * Cp >= (int64_t)1 << 31 || M * Cout >= (int64_t)1 << 40 ||
+        Cout >= (int64_t)1 << 24)
+        return FPQ_ERR_SHAPE;
+    if (!x || !packed_w || !sw || !y) return FPQ_ERR_NULL;
+    int xkind, wkind;
+    float alpha;
+    st = resolve_kinds(fx, qx.c, fw, qw.c, acc_mode, &xkind, &wkind, &alpha);
+    if (st) return st;
+    if ((reinterpret_cast<uintptr_t>(packed_w) & 15) || (reinterpret_cast<uintptr_t>(y) & 3)) return FPQ_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint8_t* xcodes;
+    if (x_is_fp32) {
+        size_t need = conv_out ? fpq_conv2d_workspace_size(B, Cin, H, W, Cout, kh, kw, stride, pad, 1)
+                               : fpq_gemm_workspace_size(M, Cout, Cin, 1);
+        if (!workspace || workspace_bytes < need) return FPQ_ERR_WORKSPACE;
+        if (reinterpret_cast<uintptr_t>(workspace) & 255) return FPQ_ERR_ALIGN;
+        if (reinterpret_cast<uintptr_t>(x) & 3) return FPQ_ERR_ALIGN;
+        uint8_t* buf = static_cast<uint8_t*>(workspace);
+        if (conv_out) {
+            st = launch_quantize_nhwc(static_cast<const float*>(x), B, Cin, H, W, qx, sx, sx_dev, buf, s);
+        } else if (Cp == Cin) {
+            st = launch_quantize(static_cast<const float*>(x), (size_t)M * Cin, qx, false, sx, sx_dev, buf, s);
+        } else {
+            // rows padded to Cp codes: a linear layer is a 1x1 "image" per row with Cin channels
+            st = launch_quantize_nhwc(static_cast<const float*>(x), M, Cin, 1, 1, qx, sx, sx_dev, buf, s);
+        }
+        if (st) return st;
+        xcodes = buf;
+    } else {
+        if (!conv_out && Cp != Cin) return FPQ_ERR_ALIGN;
+        if (reinterpret_cast<uintptr_t>(x) & 15) return FPQ_ERR_ALIGN;
+        xcodes = static_cast<const uint8_t*>(x);
+    }
+    GemmArgs a;
+    memset(&a, 0, sizeof a);
+    a.x = xcodes;
+    a.wrows = static_cast<const uint8_t*>(packed_w) + sizeof(PackedHeader);
+    a.sw = sw;
+    a.bias = bias;
+    a.sx_dev = sx_dev;
+    a.sx = sx;
+    a.alpha = alpha;
+    a.y = y;
+    a.M = (int)M;
+    a.N = (int)Cout;
+    a.Kpad = (int)padded_k(Cin, (int64_t)kh * kw);
+    a.Kreal = (int)(Cp * kh * kw);
+    a.B = (int)B; a.H = (int)H; a.W = (int)W; a.Cp = (int)Cp;
+    a.Ho = (int)Ho; a.Wo = (int)Wo;
+    a.kh = kh; a.kw = kw; a.stride = stride; a.pad = pad;
+    a.conv_out = conv_out;
+    a.xkind = xkind; a.wkind = wkind;
+    a.xe = fx.ebits; a.xm = fx.mbits; a.xb = fx.bias;
+    a.we = fw.ebits; a.wm = fw.mbits; a.wb = fw.bias;
+    a.acc_mode = acc_mode;
+    return launch_gemm(a, s);
+}
+
+int fpq_gemm(const void* x, int x_is_fp32, fpq_format_t fx, float sx, const float* sx_dev, const void* packed_w,
+             fpq_format_t fw, const float* sw, const float* bias, float* y, int64_t M, int64_t N, int64_t K,
+             int acc_mode, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (M == 0 && N > 0 && K > 0) return FPQ_OK;
+    if (M > 0 && M > 65535 && x_is_fp32 && padded_channels(K) != K) return FPQ_ERR_UNSUPPORTED;
+    return run_layer(x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, y, M, K, 1, 1, N, 1, 1, 1, 0, 0, acc_mode,
+                     workspace, workspace_bytes, stream);
+}
+
+int fpq_conv2d(const void* x, int x_is_fp32, fpq_format_t fx, float sx, const float* sx_dev, const void* packed_w,
+               fpq_format_t fw, const float* sw, const float* bias, float* y, int64_t B, int64_t Cin, int64_t H,
+               int64_t W, int64_t Cout, int kh, int kw, int stride, int pad, int acc_mode, void* workspace,
+               size_t workspace_bytes, void* stream)
+{
+    return run_layer(x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, y, B, Cin, H, W, Cout, kh, kw, stride, pad,
+                     1, acc_mode, workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,84 @@
+// Host-side declarations shared by the libfpq translation units: buffer geometry, the packed
+// weight header, and the kernel launchers that api.hip calls after validating arguments.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/fpq.h"
+
+namespace fpq {
+
+struct QParams;
+
+// Channels of a channels-last code buffer: C rounded up to a whole 16-byte chunk.
+static inline int64_t padded_channels(int64_t C) { return (C + 15) / 16 * 16; }
+
+// Length of a packed weight row: taps * Cp rounded up to the 128-code K step of the kernels.
+static inline int64_t padded_k(int64_t Cin, int64_t taps) { return (taps * padded_channels(Cin) + 127) / 128 * 128; }
+
+// Blocks of the first absmax pass (each folds >= 4096 elements; at most 1024 partials).
+static inline int absmax_parts(size_t n)
+{
+    size_t g = (n + 4095) / 4096;
+    return (int)(g > 1024 ? 1024 : g);
+}
+
+// 64-byte header in front of the packed rows.
+struct PackedHeader {
+    uint32_t magic;      // 'FPQW'
+    uint32_t layout;     // 1
+    int32_t ebits, mbits, bias;
+    float maxval;
+    int64_t N, Cin;
+    int32_t kh, kw;
+    int32_t Cp, Kpad;
+    uint32_t reserved[2];
+};
+static_assert(sizeof(PackedHeader) == 64, "header is 64 bytes");
+constexpr uint32_t kPackedMagic = 0x57515046u;
+
+// How an operand's codes reach the matrix unit.
+enum OperandKind : int {
+    OPK_FP8 = 0,      // (4, 3, b): hardware E4M3 bit pattern, value * 2^(7 - b)
+    OPK_BF8 = 1,      // (5, 2, b): hardware E5M2 bit pattern, value * 2^(15 - b)
+    OPK_FP4 = 2,      // (2, 1, b): hardware E2M1 bit pattern, value * 2^(1 - b), two codes per byte
+    OPK_GENERIC8 = 3, // any other format, one code per byte, decoded arithmetically
+    OPK_GENERIC4 = 4  // any other format of <= 4 bits, two codes per byte, decoded arithmetically
+};
+
+struct GemmArgs {
+    const uint8_t* x;       // activation codes, channels-last [B, H, W, Cp] (linear: [M, K])
+    const uint8_t* wrows;   // packed weight rows (after the header)
+    const float* sw;        // [N]
+    const float* bias;      // [N] or null
+    const float* sx_dev;    // device scale or null
+    float sx;               // host scale (used when sx_dev is null)
+    float alpha;            // power of two that maps hardware-decoded values to format values
+    float* y;
+    int M, N;               // GEMM sizes (M = B * Ho * Wo)
+    int Kpad;               // packed row length in codes
+    int Kreal;              // taps * Cp: codes of x that exist
+    int B, H, W, Cp;        // activation geometry (linear: B = M, H = W = 1)
+    int Ho, Wo;
+    int kh, kw, stride, pad;
+    int conv_out;           // 1: y is NCHW [B, N, Ho, Wo]; 0: y is [M, N]
+    int xkind, wkind;       // OperandKind
+    int xe, xm, xb;         // activation format (for the generic decode)
+    int we, wm, wb;         // weight format
+    int acc_mode;
+};
+
+int launch_absmax(const float* x, size_t n, float maxval, float* absmax_out, float* scale_out, float* partial,
+                  hipStream_t st);
+int launch_quantize(const float* x, size_t n, const QParams& q, bool four_bit, float scale, const float* scale_dev,
+                    uint8_t* codes, hipStream_t st);
+int launch_quantize_nhwc(const float* x, int64_t B, int64_t C, int64_t H, int64_t W, const QParams& q, float scale,
+                         const float* scale_dev, uint8_t* codes, hipStream_t st);
+int launch_dequantize(const uint8_t* codes, size_t n, int e, int m, int b, float scale, float* out, hipStream_t st);
+int launch_pack_weights(const float* w, int64_t N, int64_t Cin, int taps, const QParams& q, bool four_bit,
+                        const float* scale_in, const uint8_t* mask, uint8_t* packed_rows, float* scale_out,
+                        uint8_t* codes_out, hipStream_t st);
+int launch_gemm(const GemmArgs& a, hipStream_t st);
+
+}  // namespace fpq

@@ -1,0 +1,461 @@
+// Quantized linear / convolution layer on ExMy codes for gfx950 (Section V-B: Y^q = W^q A).
+//
+// One kernel template serves linear layers and convolutions (implicit GEMM with M = B*Ho*Wo,
+// K = kh*kw*Cp, N = Cout).  A workgroup of four wavefronts owns a BX x BW tile of the output
+// (BX activation rows, BW weight rows) and walks K in steps of 128 codes:
+//   global memory --16-byte loads--> registers --> LDS (xor-swizzled 16-byte chunks, two stages)
+//   LDS --16-byte reads--> registers --> MFMA 32x32 blocks, fp32 accumulators
+//   epilogue: acc * (sx * alpha * sw[n]) + bias[n], stored so that the 32 lanes of a half-wave
+//   write consecutive addresses (along n for linear output, along the pixel index for NCHW output,
+//   which is why a convolution feeds the weights as the MFMA row operand).
+// Codes stay codes (1 byte, or 4 bits for FP4 weights) all the way into registers.  Two arithmetic
+// back ends consume them:
+//   ACC_FP32      codes are expanded to bf16 in registers (hardware scaled converts for E4M3 /
+//                 E2M1 bit patterns, shifts and one multiply for any other ExMy) and multiplied by
+//                 the bf16 MFMA, whose fp32 accumulation keeps every product bit;
+//   ACC_FP8_MFMA  codes are fed to the 8-bit / 4-bit MFMA (32x32x64) directly.
+// K ordering inside a 128-code step is private to this file: any order is valid as long as both
+// operands use the same one, and each back end picks the order its register layout wants.
+#include "fpq_dev.h"
+#include "fpq_host.h"
+
+namespace fpq {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+
+// ---------------------------------------------------------------------------------- LDS geometry
+
+// Byte offset of 16-byte chunk c of a tile row.  Rows are ROWB (128 or 64) bytes; the chunk index
+// is xor-ed with bits of the row so that the lanes of a half-wave, which read the same chunk of 32
+// consecutive rows, spread over all LDS banks.
+template <int ROWB>
+__device__ __forceinline__ int lds_off(int row, int c)
+{
+    if (ROWB == 128) return row * 128 + ((c ^ ((row >> 1) & 7)) << 4);
+    return row * 64 + ((c ^ ((row >> 2) & 3)) << 4);
+}
+
+// ---------------------------------------------------------------------------------- code -> bf16
+
+// Eight codes (two dwords for one-code-per-byte operands, one dword for 4-bit operands) to the
+// bf16x8 fragment of one MFMA k-step.  KIND selects the decoder.
+struct GenFmt {
+    int e, m, b;
+};
+
+__device__ __forceinline__ uint32_t generic_pair(uint32_t c0, uint32_t c1, const GenFmt& f)
+{
+    // fp32 bit pattern with the code's exponent/mantissa fields in place has the value
+    // 2^(p-127) (1 + f/2^m) for p >= 1 and the fp32 subnormal f 2^(-126-m) for p = 0; multiplying by
+    // 2^(127-b) (as 2^64 * 2^(63-b), both representable for |b| <= 64) yields Eq. (5) and its
+    // subnormal row alike.  The result has at most 7 significant bits, so the upper half of the
+    // fp32 word is its exact bf16.
+    const uint32_t magmask = (1u << (f.e + f.m)) - 1u;
+    const float k1 = __uint_as_float((uint32_t)(127 + 64) << 23);        // 2^64
+    const float k2 = __uint_as_float((uint32_t)(127 + 63 - f.b) << 23);  // 2^(63-b)
+    float v0 = __uint_as_float((c0 & magmask) << (23 - f.m)) * k1 * k2;
+    float v1 = __uint_as_float((c1 & magmask) << (23 - f.m)) * k1 * k2;
+    uint32_t b0 = (__float_as_uint(v0) >> 16) | (((c0 >> (f.e + f.m)) & 1u) << 15);
+    uint32_t b1 = (__float_as_uint(v1) >> 16) | (((c1 >> (f.e + f.m)) & 1u) << 15);
+    return b0 | (b1 << 16);
+}
+
+template <int KIND>
+__device__ __forceinline__ v8bf decode8(uint32_t lo, uint32_t hi, const GenFmt& f)
+{
+    union {
+        v8bf v;
+        v2bf p[4];
+        uint32_t u[4];
+    } o;
+    if constexpr (KIND == OPK_FP8) {
+        o.p[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, false);
+        o.p[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, true);
+        o.p[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, false);
+        o.p[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, true);
+    } else if constexpr (KIND == OPK_BF8) {
+        o.p[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_bf8(lo, 1.0f, false);
+        o.p[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_bf8(lo, 1.0f, true);
+        o.p[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_bf8(hi, 1.0f, false);
+        o.p[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_bf8(hi, 1.0f, true);
+    } else if constexpr (KIND == OPK_FP4) {   // eight 4-bit codes in lo
+        o.p[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(lo, 1.0f, 0);
+        o.p[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(lo, 1.0f, 1);
+        o.p[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(lo, 1.0f, 2);
+        o.p[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(lo, 1.0f, 3);
+    } else if constexpr (KIND == OPK_GENERIC8) {
+        o.u[0] = generic_pair(lo & 0xffu, (lo >> 8) & 0xffu, f);
+        o.u[1] = generic_pair((lo >> 16) & 0xffu, lo >> 24, f);
+        o.u[2] = generic_pair(hi & 0xffu, (hi >> 8) & 0xffu, f);
+        o.u[3] = generic_pair((hi >> 16) & 0xffu, hi >> 24, f);
+    } else {   // OPK_GENERIC4: eight 4-bit codes in lo
+        o.u[0] = generic_pair(lo & 0xfu, (lo >> 4) & 0xfu, f);
+        o.u[1] = generic_pair((lo >> 8) & 0xfu, (lo >> 12) & 0xfu, f);
+        o.u[2] = generic_pair((lo >> 16) & 0xfu, (lo >> 20) & 0xfu, f);
+        o.u[3] = generic_pair((lo >> 24) & 0xfu, lo >> 28, f);
+    }
+    return o.v;
+}
+
+constexpr bool kind_is_4bit(int k) { return k == OPK_FP4 || k == OPK_GENERIC4; }
+// Format selector of the f8f6f4 MFMA: 0 = E4M3, 1 = E5M2, 4 = E2M1.
+constexpr int mfma_fmt(int k) { return k == OPK_FP8 ? 0 : (k == OPK_BF8 ? 1 : 4); }
+
+// ---------------------------------------------------------------------------------- the kernel
+
+template <int BX, int BW, int WGX, int WGW, int XKIND, int WKIND, int ACC, bool CONV>
+__global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a)
+{
+    constexpr bool W4 = kind_is_4bit(WKIND);
+    constexpr int XROWB = 128;                 // bytes of one activation tile row per K step
+    constexpr int WROWB = W4 ? 64 : 128;
+    constexpr int XTILE = BX * XROWB;
+    constexpr int WTILE = BW * WROWB;
+    constexpr int STAGE = XTILE + WTILE;
+    constexpr int XLD = BX / 32;               // 16-byte chunks per lane and stage, activations
+    constexpr int WCPR = WROWB / 16;           // chunks per weight row
+    constexpr int WROWS_PER_PASS = 256 / WCPR;
+    constexpr int WLD = (BW + WROWS_PER_PASS - 1) / WROWS_PER_PASS;
+    // MFMA row operand P and lane operand Q: linear output wants lanes along n (P = activations),
+    // NCHW output wants lanes along the pixel index (P = weights).
+    constexpr int BP = CONV ? BW : BX, BQ = CONV ? BX : BW;
+    constexpr int WGP = CONV ? WGW : WGX, WGQ = CONV ? WGX : WGW;
+    constexpr int TP = BP / WGP, TQ = BQ / WGQ;
+    constexpr int MI = TP / 32, NI = TQ / 32;
+    static_assert(WGX * WGW == 4 && TP % 32 == 0 && TQ % 32 == 0, "tile shape");
+    constexpr int PKIND = CONV ? WKIND : XKIND, QKIND = CONV ? XKIND : WKIND;
+    constexpr int PROWB = CONV ? WROWB : XROWB, QROWB = CONV ? XROWB : WROWB;
+    constexpr bool P4 = kind_is_4bit(PKIND), Q4 = kind_is_4bit(QKIND);
+    constexpr int PFMT = mfma_fmt(PKIND), QFMT = mfma_fmt(QKIND);   // immediates of the MFMA
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int l32 = lane & 31;
+    const int g = lane >> 5;
+
+    // Workgroup -> tile.  Consecutive workgroup ids go round-robin over the 8 XCDs; regroup them so
+    // that each XCD (one L2) works on a contiguous run of tiles that share activation rows.
+    const int tiles_w = (a.N + BW - 1) / BW;
+    const int tiles_x = (a.M + BX - 1) / BX;
+    const int ntiles = tiles_w * tiles_x;
+    int bid = blockIdx.x;
+    {
+        const int per = ntiles >> 3;
+        if (bid < (per << 3)) bid = (bid & 7) * per + (bid >> 3);
+    }
+    const int tx = bid / tiles_w, tw = bid - tx * tiles_w;
+    const int m0 = tx * BX, n0 = tw * BW;
+
+    // ---- per-lane load bookkeeping
+    const int xc = tid & 7;                    // chunk column of this lane in the activation tile
+    const int xr0 = tid >> 3;                  // first row; further rows are +32
+    int xbase[XLD];                            // code offset of (pixel, channel 0), tap (0,0)
+    int xhw[XLD];                              // (hi0 + 0x4000) << 16 | (wi0 + 0x4000), or -1 if row >= M
+#pragma unroll
+    for (int i = 0; i < XLD; ++i) {
+        const int m = m0 + xr0 + 32 * i;
+        if (m < a.M) {
+            if (CONV) {
+                const int hw = a.Ho * a.Wo;
+                const int bi = m / hw;
+                const int rem = m - bi * hw;
+                const int ho = rem / a.Wo, wo = rem - ho * a.Wo;
+                const int hi0 = ho * a.stride - a.pad, wi0 = wo * a.stride - a.pad;
+                xbase[i] = ((bi * a.H + hi0) * a.W + wi0) * a.Cp;
+                xhw[i] = ((hi0 + 0x4000) << 16) | (wi0 + 0x4000);
+            } else {
+                xbase[i] = m * a.Cp;
+                xhw[i] = 0;
+            }
+        } else {
+            xbase[i] = 0;
+            xhw[i] = -1;
+        }
+    }
+    int x_ci = xc * 16, x_kh = 0, x_kw = 0, x_k = xc * 16;   // K position of this lane's chunk
+    if (CONV) {
+        while (x_ci >= a.Cp) {
+            x_ci -= a.Cp;
+            if (++x_kw == a.kw) { x_kw = 0; ++x_kh; }
+        }
+    }
+    const int wc = tid % WCPR;
+    const int wr0 = tid / WCPR;
+    const size_t wrow_bytes = W4 ? (size_t)a.Kpad / 2 : (size_t)a.Kpad;
+
+    uint4 xreg[XLD], wreg[WLD];
+
+    auto load_global = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < XLD; ++i) {
+            bool ok = (xhw[i] != -1) && (x_k < a.Kreal);
+            int off;
+            if (CONV) {
+                const int hi = (xhw[i] >> 16) - 0x4000 + x_kh, wi = (xhw[i] & 0xffff) - 0x4000 + x_kw;
+                ok = ok && ((unsigned)hi < (unsigned)a.H) && ((unsigned)wi < (unsigned)a.W);
+                off = xbase[i] + (x_kh * a.W + x_kw) * a.Cp + x_ci;
+            } else {
+                off = xbase[i] + x_k;
+            }
+            xreg[i] = ok ? *reinterpret_cast<const uint4*>(a.x + off) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < WLD; ++i) {
+            const int row = wr0 + WROWS_PER_PASS * i;
+            const int n = n0 + row;
+            const bool ok = (row < BW) && (n < a.N);
+            wreg[i] = ok ? *reinterpret_cast<const uint4*>(a.wrows + (size_t)n * wrow_bytes +
+                                                          (size_t)kt * WROWB + wc * 16)
+                         : make_uint4(0, 0, 0, 0);
+        }
+        // advance this lane's K position by one step
+        x_k += 128;
+        if (CONV) {
+            x_ci += 128;
+            while (x_ci >= a.Cp) {
+                x_ci -= a.Cp;
+                if (++x_kw == a.kw) { x_kw = 0; ++x_kh; }
+            }
+        }
+    };
+    auto store_lds = [&](int stage) {
+        uint8_t* xs = smem + stage * STAGE;
+        uint8_t* ws = xs + XTILE;
+#pragma unroll
+        for (int i = 0; i < XLD; ++i)
+            *reinterpret_cast<uint4*>(xs + lds_off<XROWB>(xr0 + 32 * i, xc)) = xreg[i];
+#pragma unroll
+        for (int i = 0; i < WLD; ++i) {
+            const int row = wr0 + WROWS_PER_PASS * i;
+            if (row < BW) *reinterpret_cast<uint4*>(ws + lds_off<WROWB>(row, wc)) = wreg[i];
+        }
+    };
+
+    // ---- accumulators
+    v16f acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int wp = CONV ? (wave % WGW) : (wave / WGW);   // wave coordinate along P
+    const int wq = CONV ? (wave / WGW) : (wave % WGW);   // wave coordinate along Q
+    const int prow0 = wp * TP + l32;
+    const int qrow0 = wq * TQ + l32;
+    const GenFmt pf = CONV ? GenFmt{a.we, a.wm, a.wb} : GenFmt{a.xe, a.xm, a.xb};
+    const GenFmt qf = CONV ? GenFmt{a.xe, a.xm, a.xb} : GenFmt{a.we, a.wm, a.wb};
+
+    auto compute = [&](int stage) {
+        const uint8_t* xs = smem + stage * STAGE;
+        const uint8_t* ws = xs + XTILE;
+        const uint8_t* ps = CONV ? ws : xs;
+        const uint8_t* qs = CONV ? xs : ws;
+        if constexpr (ACC == FPQ_ACC_FP32) {
+            // 128 codes = 4 rounds; in round j lane half g holds codes (2j+g)*16 .. +15 of the row and
+            // feeds them to two bf16 k-steps of 8 codes each.
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint4 praw[MI], qraw[NI];
+#pragma unroll
+                for (int i = 0; i < MI; ++i) {
+                    const int row = prow0 + 32 * i;
+                    if (P4) {
+                        uint2 v = *reinterpret_cast<const uint2*>(ps + lds_off<PROWB>(row, j) + g * 8);
+                        praw[i] = make_uint4(v.x, v.y, 0, 0);
+                    } else {
+                        praw[i] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 2 * j + g));
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < NI; ++i) {
+                    const int row = qrow0 + 32 * i;
+                    if (Q4) {
+                        uint2 v = *reinterpret_cast<const uint2*>(qs + lds_off<QROWB>(row, j) + g * 8);
+                        qraw[i] = make_uint4(v.x, v.y, 0, 0);
+                    } else {
+                        qraw[i] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 2 * j + g));
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    v8bf pfr[MI], qfr[NI];
+#pragma unroll
+                    for (int i = 0; i < MI; ++i)
+                        pfr[i] = P4 ? decode8<PKIND>(t ? praw[i].y : praw[i].x, 0u, pf)
+                                    : decode8<PKIND>(t ? praw[i].z : praw[i].x, t ? praw[i].w : praw[i].y, pf);
+#pragma unroll
+                    for (int i = 0; i < NI; ++i)
+                        qfr[i] = Q4 ? decode8<QKIND>(t ? qraw[i].y : qraw[i].x, 0u, qf)
+                                    : decode8<QKIND>(t ? qraw[i].z : qraw[i].x, t ? qraw[i].w : qraw[i].y, qf);
+#pragma unroll
+                    for (int i = 0; i < MI; ++i)
+#pragma unroll
+                        for (int jj = 0; jj < NI; ++jj)
+                            acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pfr[i], qfr[jj], acc[i][jj], 0, 0, 0);
+                }
+            }
+        } else {
+            // 128 codes = two 64-code MFMA steps.  Within a step the instruction pairs byte i < 16 of an
+            // 8-bit operand (lane half g) with K index 16g + i and byte 16 + i with 32 + 16g + i, and nibble
+            // i of a 4-bit operand with K index 32g + i; the chunk choices below follow from that.
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                v8i pfr[MI], qfr[NI];
+#pragma unroll
+                for (int i = 0; i < MI; ++i) {
+                    const int row = prow0 + 32 * i;
+                    union { v8i v; uint4 q[2]; } u;
+                    if (P4) {
+                        u.q[0] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 2 * kk + g));
+                        u.q[1] = make_uint4(0, 0, 0, 0);
+                    } else {
+                        u.q[0] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 4 * kk + g));
+                        u.q[1] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 4 * kk + 2 + g));
+                    }
+                    pfr[i] = u.v;
+                }
+#pragma unroll
+                for (int i = 0; i < NI; ++i) {
+                    const int row = qrow0 + 32 * i;
+                    union { v8i v; uint4 q[2]; } u;
+                    if (Q4) {
+                        u.q[0] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 2 * kk + g));
+                        u.q[1] = make_uint4(0, 0, 0, 0);
+                    } else {
+                        u.q[0] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 4 * kk + g));
+                        u.q[1] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 4 * kk + 2 + g));
+                    }
+                    qfr[i] = u.v;
+                }
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int jj = 0; jj < NI; ++jj)
+                        acc[i][jj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                            pfr[i], qfr[jj], acc[i][jj], PFMT, QFMT, 0, 0, 0, 0);
+            }
+        }
+    };
+
+    // ---- main loop: two LDS stages, next step's global loads in flight during the MFMAs
+    const int nk = a.Kpad / 128;
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) load_global(kt + 1);
+        compute(cur);
+        if (kt + 1 < nk) store_lds(cur ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue
+    const float sxa = (a.sx_dev ? a.sx_dev[0] : a.sx) * a.alpha;
+    if (!CONV) {
+        // P = activations: acc[i][j][r] is (m, n) = (row block i, r -> 8(r/4) + 4g + r%4 ; lane -> n)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int n = n0 + wq * TQ + 32 * j + l32;
+            if (n >= a.N) continue;
+            const float sc = sxa * a.sw[n];
+            const float bv = a.bias ? a.bias[n] : 0.0f;
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + wp * TP + 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
+                    if (m < a.M) a.y[(size_t)m * a.N + n] = acc[i][j][r] * sc + bv;
+                }
+        }
+    } else {
+        // P = weights: rows are n, lanes are pixels m
+        const int hw = a.Ho * a.Wo;
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int m = m0 + wq * TQ + 32 * j + l32;
+            if (m >= a.M) continue;
+            const int bi = m / hw;
+            const int pix = m - bi * hw;
+            float* ybase = a.y + (size_t)bi * a.N * hw + pix;
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int n = n0 + wp * TP + 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
+                    if (n < a.N) {
+                        const float sc = sxa * a.sw[n];
+                        const float bv = a.bias ? a.bias[n] : 0.0f;
+                        ybase[(size_t)n * hw] = acc[i][j][r] * sc + bv;
+                    }
+                }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------- dispatch
+
+template <int BX, int BW, int WGX, int WGW, int XKIND, int WKIND, int ACC, bool CONV>
+static int launch_one(const GemmArgs& a, hipStream_t st)
+{
+    constexpr int WROWB = kind_is_4bit(WKIND) ? 64 : 128;
+    constexpr int smem = 2 * (BX * 128 + BW * WROWB);
+    const int tiles = ((a.M + BX - 1) / BX) * ((a.N + BW - 1) / BW);
+    auto kern = gemm_kernel<BX, BW, WGX, WGW, XKIND, WKIND, ACC, CONV>;
+    if (smem > 64 * 1024) {
+        static bool raised = false;   // per instantiation
+        if (!raised) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    smem) != hipSuccess)
+                return FPQ_ERR_LAUNCH;
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3(tiles), dim3(256), smem, st, a);
+    return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
+}
+
+template <int XKIND, int WKIND, int ACC, bool CONV>
+static int launch_tiles(const GemmArgs& a, hipStream_t st)
+{
+    // Tile choice: the large tile when it still yields at least two waves of workgroups over the 256
+    // compute units, otherwise the small one.
+    const long big = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
+    if (big >= 512) return launch_one<128, 128, 2, 2, XKIND, WKIND, ACC, CONV>(a, st);
+    return launch_one<64, 64, 2, 2, XKIND, WKIND, ACC, CONV>(a, st);
+}
+
+template <int XKIND, int WKIND, int ACC>
+static int launch_conv_or_linear(const GemmArgs& a, hipStream_t st)
+{
+    return a.conv_out ? launch_tiles<XKIND, WKIND, ACC, true>(a, st) : launch_tiles<XKIND, WKIND, ACC, false>(a, st);
+}
+
+int launch_gemm(const GemmArgs& a, hipStream_t st)
+{
+    if (a.M <= 0 || a.N <= 0) return FPQ_OK;
+    if (a.acc_mode == FPQ_ACC_FP8_MFMA) {
+        if (a.xkind == OPK_FP8 && a.wkind == OPK_FP8) return launch_conv_or_linear<OPK_FP8, OPK_FP8, FPQ_ACC_FP8_MFMA>(a, st);
+        if (a.xkind == OPK_FP8 && a.wkind == OPK_FP4) return launch_conv_or_linear<OPK_FP8, OPK_FP4, FPQ_ACC_FP8_MFMA>(a, st);
+        if (a.xkind == OPK_FP8 && a.wkind == OPK_BF8) return launch_conv_or_linear<OPK_FP8, OPK_BF8, FPQ_ACC_FP8_MFMA>(a, st);
+        if (a.xkind == OPK_BF8 && a.wkind == OPK_FP8) return launch_conv_or_linear<OPK_BF8, OPK_FP8, FPQ_ACC_FP8_MFMA>(a, st);
+        if (a.xkind == OPK_BF8 && a.wkind == OPK_BF8) return launch_conv_or_linear<OPK_BF8, OPK_BF8, FPQ_ACC_FP8_MFMA>(a, st);
+        if (a.xkind == OPK_BF8 && a.wkind == OPK_FP4) return launch_conv_or_linear<OPK_BF8, OPK_FP4, FPQ_ACC_FP8_MFMA>(a, st);
+        return FPQ_ERR_UNSUPPORTED;
+    }
+    if (a.xkind == OPK_FP8 && a.wkind == OPK_FP8) return launch_conv_or_linear<OPK_FP8, OPK_FP8, FPQ_ACC_FP32>(a, st);
+    if (a.xkind == OPK_FP8 && a.wkind == OPK_FP4) return launch_conv_or_linear<OPK_FP8, OPK_FP4, FPQ_ACC_FP32>(a, st);
+    // every other pairing: arithmetic decode of both operands
+    if (kind_is_4bit(a.wkind)) return launch_conv_or_linear<OPK_GENERIC8, OPK_GENERIC4, FPQ_ACC_FP32>(a, st);
+    return launch_conv_or_linear<OPK_GENERIC8, OPK_GENERIC8, FPQ_ACC_FP32>(a, st);
+}
+
+}  // namespace fpq

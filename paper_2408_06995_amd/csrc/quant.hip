@@ -1,0 +1,322 @@
+// Streaming kernels of libfpq: absmax calibration, the activation quantizer (flat and
+// NCHW -> channels-last), dequantize, and the offline weight quantizer / packer.
+// All are HBM-bound: 16-byte coalesced loads, the ExMy encode in registers, packed stores.
+#include "fpq_dev.h"
+#include "fpq_host.h"
+
+namespace fpq {
+
+// ------------------------------------------------------------------------------ absmax
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+__device__ __forceinline__ float block_max(float v)
+{
+    __shared__ float part[4];
+    v = wave_max(v);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = v;
+    __syncthreads();
+    v = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
+    __syncthreads();
+    return v;
+}
+
+// Pass 1: each block folds a grid-strided share of x into one partial maximum of |x|.
+__global__ __launch_bounds__(256) void absmax_partial_kernel(const float* __restrict__ x, size_t n,
+                                                             float* __restrict__ partial)
+{
+    float v = 0.0f;
+    const size_t tid = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t nthreads = (size_t)gridDim.x * 256;
+    if ((reinterpret_cast<uintptr_t>(x) & 15) == 0) {
+        const float4* x4 = reinterpret_cast<const float4*>(x);
+        const size_t n4 = n >> 2;
+        size_t i = tid;
+        for (; i + 3 * nthreads < n4; i += 4 * nthreads) {
+            float4 a = x4[i], b = x4[i + nthreads], c = x4[i + 2 * nthreads], d = x4[i + 3 * nthreads];
+            v = fmaxf(v, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+            v = fmaxf(v, fmaxf(fmaxf(fabsf(b.x), fabsf(b.y)), fmaxf(fabsf(b.z), fabsf(b.w))));
+            v = fmaxf(v, fmaxf(fmaxf(fabsf(c.x), fabsf(c.y)), fmaxf(fabsf(c.z), fabsf(c.w))));
+            v = fmaxf(v, fmaxf(fmaxf(fabsf(d.x), fabsf(d.y)), fmaxf(fabsf(d.z), fabsf(d.w))));
+        }
+        for (; i < n4; i += nthreads) {
+            float4 a = x4[i];
+            v = fmaxf(v, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+        }
+        for (size_t j = (n4 << 2) + tid; j < n; j += nthreads) v = fmaxf(v, fabsf(x[j]));
+    } else {
+        for (size_t j = tid; j < n; j += nthreads) v = fmaxf(v, fabsf(x[j]));
+    }
+    v = block_max(v);
+    if (threadIdx.x == 0) partial[blockIdx.x] = v;
+}
+
+// Pass 2: one block folds the partials and writes absmax and scale = absmax / maxval.
+__global__ __launch_bounds__(256) void absmax_final_kernel(const float* __restrict__ partial, int nparts,
+                                                           float maxval, float* __restrict__ absmax_out,
+                                                           float* __restrict__ scale_out)
+{
+    float v = 0.0f;
+    for (int i = threadIdx.x; i < nparts; i += 256) v = fmaxf(v, partial[i]);
+    v = block_max(v);
+    if (threadIdx.x == 0) {
+        absmax_out[0] = v;
+        if (scale_out) scale_out[0] = (v == 0.0f) ? 1.0f : __fdiv_rn(v, maxval);
+    }
+}
+
+int launch_absmax(const float* x, size_t n, float maxval, float* absmax_out, float* scale_out,
+                  float* partial, hipStream_t st)
+{
+    int nparts = absmax_parts(n);
+    if (nparts > 0)
+        hipLaunchKernelGGL(absmax_partial_kernel, dim3(nparts), dim3(256), 0, st, x, n, partial);
+    hipLaunchKernelGGL(absmax_final_kernel, dim3(1), dim3(256), 0, st, partial, nparts, maxval, absmax_out,
+                       scale_out);
+    return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
+}
+
+// ------------------------------------------------------------------------------ quantize (flat)
+
+// Four elements per lane and step: one 16-byte load, four encodes, one 4-byte (8-bit codes) or
+// 2-byte (4-bit codes) store.  Four independent loads are kept in flight per lane.
+template <bool FOUR_BIT>
+__global__ __launch_bounds__(256) void quantize_vec_kernel(const float4* __restrict__ x4, size_t n4, QParams q,
+                                                           float scale, const float* __restrict__ scale_dev,
+                                                           uint8_t* __restrict__ codes)
+{
+    const float r = inv_scale(scale, scale_dev);
+    const size_t nthreads = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    auto emit = [&](size_t idx, const float4& v) {
+        uint32_t c0 = quantize_nearest(v.x, r, q), c1 = quantize_nearest(v.y, r, q);
+        uint32_t c2 = quantize_nearest(v.z, r, q), c3 = quantize_nearest(v.w, r, q);
+        if (FOUR_BIT)
+            reinterpret_cast<uint16_t*>(codes)[idx] = (uint16_t)(c0 | (c1 << 4) | (c2 << 8) | (c3 << 12));
+        else
+            reinterpret_cast<uint32_t*>(codes)[idx] = c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+    };
+    for (; i + 3 * nthreads < n4; i += 4 * nthreads) {
+        float4 a = x4[i], b = x4[i + nthreads], c = x4[i + 2 * nthreads], d = x4[i + 3 * nthreads];
+        emit(i, a);
+        emit(i + nthreads, b);
+        emit(i + 2 * nthreads, c);
+        emit(i + 3 * nthreads, d);
+    }
+    for (; i < n4; i += nthreads) emit(i, x4[i]);
+}
+
+// One output byte per lane: any alignment, tails.  first = index of the first element handled.
+template <bool FOUR_BIT>
+__global__ __launch_bounds__(256) void quantize_scalar_kernel(const float* __restrict__ x, size_t first, size_t n,
+                                                              QParams q, float scale,
+                                                              const float* __restrict__ scale_dev,
+                                                              uint8_t* __restrict__ codes)
+{
+    const float r = inv_scale(scale, scale_dev);
+    const size_t per = FOUR_BIT ? 2 : 1;
+    size_t j = first / per + (size_t)blockIdx.x * 256 + threadIdx.x;  // output byte
+    const size_t nbytes = (n + per - 1) / per;
+    const size_t nthreads = (size_t)gridDim.x * 256;
+    for (; j < nbytes; j += nthreads) {
+        if (FOUR_BIT) {
+            uint32_t lo = quantize_nearest(x[2 * j], r, q);
+            uint32_t hi = (2 * j + 1 < n) ? quantize_nearest(x[2 * j + 1], r, q) : 0u;
+            codes[j] = (uint8_t)(lo | (hi << 4));
+        } else {
+            codes[j] = (uint8_t)quantize_nearest(x[j], r, q);
+        }
+    }
+}
+
+static int grid_for(size_t work_items, int per_block)
+{
+    size_t g = (work_items + per_block - 1) / per_block;
+    if (g < 1) g = 1;
+    if (g > 4096) g = 4096;
+    return (int)g;
+}
+
+int launch_quantize(const float* x, size_t n, const QParams& q, bool four_bit, float scale,
+                    const float* scale_dev, uint8_t* codes, hipStream_t st)
+{
+    if (n == 0) return FPQ_OK;
+    bool aligned = (reinterpret_cast<uintptr_t>(x) & 15) == 0 && (reinterpret_cast<uintptr_t>(codes) & 3) == 0;
+    size_t n4 = aligned ? (n >> 2) : 0;
+    if (n4) {
+        int g = grid_for(n4, 256 * 4);
+        if (four_bit)
+            hipLaunchKernelGGL(quantize_vec_kernel<true>, dim3(g), dim3(256), 0, st,
+                               reinterpret_cast<const float4*>(x), n4, q, scale, scale_dev, codes);
+        else
+            hipLaunchKernelGGL(quantize_vec_kernel<false>, dim3(g), dim3(256), 0, st,
+                               reinterpret_cast<const float4*>(x), n4, q, scale, scale_dev, codes);
+    }
+    size_t first = n4 << 2;
+    if (first < n) {
+        int g = grid_for(n - first, 256);
+        if (four_bit)
+            hipLaunchKernelGGL(quantize_scalar_kernel<true>, dim3(g), dim3(256), 0, st, x, first, n, q, scale,
+                               scale_dev, codes);
+        else
+            hipLaunchKernelGGL(quantize_scalar_kernel<false>, dim3(g), dim3(256), 0, st, x, first, n, q, scale,
+                               scale_dev, codes);
+    }
+    return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
+}
+
+// ------------------------------------------------------------------- quantize NCHW -> NHWC codes
+
+// One block turns a 64-channel x 64-pixel patch of one image: reads run along pixels (contiguous in
+// NCHW), the codes cross an LDS tile, writes run along channels (contiguous in [B,H,W,Cp]).
+// Channels C..Cp-1 receive code 0.  Rows of the tile are 68 bytes so that the four-byte column
+// groups of neighbouring pixels fall into different LDS banks.
+__global__ __launch_bounds__(256) void quantize_nhwc_kernel(const float* __restrict__ x, int C, int Cp, int HW,
+                                                            QParams q, float scale,
+                                                            const float* __restrict__ scale_dev,
+                                                            uint8_t* __restrict__ codes)
+{
+    constexpr int LDW = 68;
+    __shared__ __attribute__((aligned(16))) uint8_t tile[64 * LDW];
+    const float r = inv_scale(scale, scale_dev);
+    const int b = blockIdx.z;
+    const int c0 = blockIdx.y * 64;
+    const int p0 = blockIdx.x * 64;
+    const int pq = threadIdx.x & 15;   // pixel quad
+    const int cs = threadIdx.x >> 4;   // channel within a pass
+    const bool vec_ok = ((HW & 3) == 0) && ((reinterpret_cast<uintptr_t>(x) & 15) == 0);
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+        const int cl = pass * 16 + cs;
+        const int ch = c0 + cl;
+        const int p = p0 + 4 * pq;
+        uint32_t cd[4] = {0u, 0u, 0u, 0u};
+        if (ch < C) {
+            const float* src = x + ((size_t)b * C + ch) * (size_t)HW + p;
+            if (vec_ok && p + 3 < HW) {
+                float4 v = *reinterpret_cast<const float4*>(src);
+                cd[0] = quantize_nearest(v.x, r, q);
+                cd[1] = quantize_nearest(v.y, r, q);
+                cd[2] = quantize_nearest(v.z, r, q);
+                cd[3] = quantize_nearest(v.w, r, q);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (p + j < HW) cd[j] = quantize_nearest(src[j], r, q);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) tile[(4 * pq + j) * LDW + cl] = (uint8_t)cd[j];
+    }
+    __syncthreads();
+    const int pl = threadIdx.x >> 2;
+    const int part = threadIdx.x & 3;
+    const int p = p0 + pl;
+    const int ch = c0 + part * 16;
+    if (p < HW && ch < Cp) {
+        const uint32_t* t4 = reinterpret_cast<const uint32_t*>(tile + pl * LDW + part * 16);
+        uint4 v = make_uint4(t4[0], t4[1], t4[2], t4[3]);
+        *reinterpret_cast<uint4*>(codes + ((size_t)b * HW + p) * (size_t)Cp + ch) = v;
+    }
+}
+
+int launch_quantize_nhwc(const float* x, int64_t B, int64_t C, int64_t H, int64_t W, const QParams& q,
+                         float scale, const float* scale_dev, uint8_t* codes, hipStream_t st)
+{
+    int Cp = (int)padded_channels(C);
+    int HW = (int)(H * W);
+    dim3 grid((HW + 63) / 64, (Cp + 63) / 64, (unsigned)B);
+    hipLaunchKernelGGL(quantize_nhwc_kernel, grid, dim3(256), 0, st, x, (int)C, Cp, HW, q, scale, scale_dev, codes);
+    return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
+}
+
+// ------------------------------------------------------------------------------ dequantize
+
+__global__ __launch_bounds__(256) void dequantize_kernel(const uint8_t* __restrict__ codes, size_t n, int e, int m,
+                                                         int b, float scale, float* __restrict__ out)
+{
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t nthreads = (size_t)gridDim.x * 256;
+    for (; i < n; i += nthreads) out[i] = __fmul_rn(decode_code(codes[i], e, m, b), scale);
+}
+
+int launch_dequantize(const uint8_t* codes, size_t n, int e, int m, int b, float scale, float* out, hipStream_t st)
+{
+    if (n == 0) return FPQ_OK;
+    hipLaunchKernelGGL(dequantize_kernel, dim3(grid_for(n, 256)), dim3(256), 0, st, codes, n, e, m, b, scale, out);
+    return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
+}
+
+// ------------------------------------------------------------------------------ pack weights
+
+// One block per output channel n.  The row's scale is its absmax / c unless given; every element
+// is quantized (Eq. (12) with its mask entry, or Eq. (8) without a mask) and written to the packed
+// row in (kh, kw, ci) order with ci padded to Cp and the row padded to Kpad, padding = code 0.
+// A lane builds one 4-byte word of the packed row: 4 codes, or 8 codes for 4-bit formats.
+template <bool FOUR_BIT>
+__global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restrict__ w, int Cin, int taps, int Cp,
+                                                           int Kpad, QParams q, const float* __restrict__ scale_in,
+                                                           const uint8_t* __restrict__ mask,
+                                                           uint8_t* __restrict__ packed_rows,
+                                                           float* __restrict__ scale_out,
+                                                           uint8_t* __restrict__ codes_out)
+{
+    const int n = blockIdx.x;
+    const size_t K = (size_t)Cin * taps;
+    const float* row = w + (size_t)n * K;
+    const uint8_t* mrow = mask ? mask + (size_t)n * K : nullptr;
+    float s;
+    if (scale_in) {
+        s = scale_in[n];
+    } else {
+        float v = 0.0f;
+        for (size_t i = threadIdx.x; i < K; i += 256) v = fmaxf(v, fabsf(row[i]));
+        v = block_max(v);
+        s = (v == 0.0f) ? 1.0f : __fdiv_rn(v, q.c);
+    }
+    if (threadIdx.x == 0) scale_out[n] = s;
+    const float r = __fdiv_rn(1.0f, s);
+    constexpr int GW = FOUR_BIT ? 8 : 4;
+    const size_t row_bytes = FOUR_BIT ? (size_t)Kpad / 2 : (size_t)Kpad;
+    uint32_t* dst = reinterpret_cast<uint32_t*>(packed_rows + (size_t)n * row_bytes);
+    for (int g = threadIdx.x; g < Kpad / GW; g += 256) {
+        const int kp0 = g * GW;
+        const int tap = kp0 / Cp;
+        const int ci0 = kp0 - tap * Cp;
+        uint32_t word = 0;
+#pragma unroll
+        for (int j = 0; j < GW; ++j) {
+            const int ci = ci0 + j;
+            uint32_t code = 0;
+            if (tap < taps && ci < Cin) {
+                const size_t src = (size_t)ci * taps + tap;   // [Cin, kh, kw] within the row
+                code = mrow ? quantize_mask(row[src], r, mrow[src], q) : quantize_nearest(row[src], r, q);
+                if (codes_out) codes_out[(size_t)n * K + src] = (uint8_t)code;
+            }
+            word |= code << (FOUR_BIT ? 4 * j : 8 * j);
+        }
+        dst[g] = word;
+    }
+}
+
+int launch_pack_weights(const float* w, int64_t N, int64_t Cin, int taps, const QParams& q, bool four_bit,
+                        const float* scale_in, const uint8_t* mask, uint8_t* packed_rows, float* scale_out,
+                        uint8_t* codes_out, hipStream_t st)
+{
+    int Cp = (int)padded_channels(Cin);
+    int Kpad = (int)padded_k(Cin, taps);
+    if (four_bit)
+        hipLaunchKernelGGL(pack_weights_kernel<true>, dim3((unsigned)N), dim3(256), 0, st, w, (int)Cin, taps, Cp, Kpad,
+                           q, scale_in, mask, packed_rows, scale_out, codes_out);
+    else
+        hipLaunchKernelGGL(pack_weights_kernel<false>, dim3((unsigned)N), dim3(256), 0, st, w, (int)Cin, taps, Cp,
+                           Kpad, q, scale_in, mask, packed_rows, scale_out, codes_out);
+    return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
+}
+
+}  // namespace fpq

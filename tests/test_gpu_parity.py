@@ -1,0 +1,348 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+Codes must match bit for bit; layer outputs must satisfy |gpu - oracle| <= 1e-5 * sum_k|a_k b_k| + 1e-6
+in the fp32-accumulate mode (the default), and the hardware bound 7 * 2^-13 * sum_k|a_k b_k| in the
+FP8-MFMA mode, whose matrix unit drops product bits more than 13 places below the largest of each 8."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2408_06995_amd import binding as B
+from paper_2408_06995_amd import synth
+from gpu_util import DEV, check_close, dev, gpu_absmax_scale, gpu_pack, gpu_quantize, oracle_linear_inputs
+
+pytestmark = pytest.mark.gpu
+
+FORMATS = {
+    "E4M3": synth.E4M3, "E5M2": synth.E5M2, "E2M1": synth.E2M1, "E1M2": synth.E1M2, "E3M4": synth.E3M4,
+    "E2M5": synth.E2M5, "E3M0": synth.E3M0, "E4M3_eq7": (4, 3, 7, 480.0), "E4M3_b9": (4, 3, 9, 112.0),
+    "E5M2_eq7": (5, 2, 15, 0.0), "E2M1_b2": (2, 1, 2, 3.0), "E3M2": (3, 2, 3, 28.0), "E1M6": (1, 6, 1, 0.0),
+    "E4M3_bneg": (4, 3, -3, 0.0), "E2M3_sub": (2, 3, 1, 0.875),
+}
+REL_FP8_MFMA = 7 * 2.0 ** -13
+
+
+def resolved(f):
+    e, m, b, c = f
+    return (e, m, b, c if c else oracle.format_max(e, m, b))
+
+
+def edge_values(f, scale):
+    e, m, b, c = resolved(f)
+    g = oracle.grid((e, m, b, c))
+    g = g[g <= c]
+    mids = (g[:-1] + g[1:]) / 2
+    v = np.concatenate([g, mids, [c * 1.01, c * 4, 0.0]]).astype(np.float32)
+    v = np.concatenate([v, np.nextafter(v, np.float32(np.inf)), np.nextafter(v, np.float32(-np.inf))])
+    v = np.concatenate([v, -v, np.array([np.inf, -np.inf, -0.0, 1e-45, -1e-45, 1e-38, 3e38], dtype=np.float32)])
+    return (v.astype(np.float64) * float(scale)).astype(np.float32)
+
+
+# ------------------------------------------------------------------------------ quantizer
+
+@pytest.mark.parametrize("name", sorted(FORMATS))
+def test_quantize_codes_bit_exact(name):
+    f = resolved(FORMATS[name])
+    rng = np.random.default_rng(abs(hash(name)) % 2 ** 31)
+    four = 1 + f[0] + f[1] <= 4
+    for scale in (1.0, 0.0371, 2.0 ** -4, 5.3):
+        scale = float(np.float32(scale))
+        x = np.concatenate([synth.activations((70001,), 11) * np.float32(scale * f[3] / 4),
+                            rng.uniform(-1.5, 1.5, 30000).astype(np.float32) * np.float32(scale * f[3]),
+                            edge_values(f, scale), edge_values(f, 1.0)])
+        want = oracle.quantize(x, f, scale)
+        got = gpu_quantize(x, f, scale)
+        if four:
+            want = oracle.pack4(want)
+        assert got.shape == want.shape
+        assert np.array_equal(got, want), "%s scale %g: %d codes differ" % (name, scale, int((got != want).sum()))
+    # device-resident scale gives the same codes
+    x = synth.activations((4099,), 12)
+    sd = dev(np.array([0.0371], dtype=np.float32))
+    got = gpu_quantize(x, f, None, sd)
+    want = oracle.quantize(x, f, float(np.float32(0.0371)))
+    assert np.array_equal(got, oracle.pack4(want) if four else want)
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 7, 63, 255, 1023, 4097, 262147])
+def test_quantize_ragged_sizes_and_alignment(n):
+    for f in (synth.E4M3, synth.E2M1):
+        x = synth.activations((n + 3,), 100 + n)
+        for off in (0, 1):                       # off = 1: 4-byte-aligned but not 16-byte-aligned input
+            xs = x[off:off + n]
+            xt = dev(x)[off:off + n]
+            codes = torch.full((B.fpq_code_bytes(n, f) + 8,), 0xEE, dtype=torch.uint8, device=DEV)
+            B.fpq_quantize(xt, f, 0.02, None, codes[4:])
+            torch.cuda.synchronize()
+            got = codes.cpu().numpy()
+            want = oracle.quantize(xs, f, float(np.float32(0.02)))
+            if f is synth.E2M1:
+                want = oracle.pack4(want)
+            assert np.array_equal(got[4:4 + want.size], want)
+            assert np.all(got[:4] == 0xEE) and np.all(got[4 + want.size:] == 0xEE)   # nothing written outside
+
+
+def test_quantize_strided_sweep_of_all_fp32_patterns():
+    """Every 257th fp32 bit pattern (16.7 M inputs: all exponents, denormals, both signs, infinities)."""
+    bits = np.arange(0, 2 ** 32, 257, dtype=np.uint64).astype(np.uint32)
+    x = bits.view(np.float32)
+    x = x[~np.isnan(x)]
+    for f, scale in ((synth.E4M3, 1.0), (synth.E4M3, 0.7331), (synth.E3M4, 1.0), (synth.E2M1, 3.0e-3), (synth.E5M2, 1e-30)):
+        scale = float(np.float32(scale))
+        want = oracle.quantize(x, f, scale)
+        if 1 + f[0] + f[1] <= 4:
+            want = oracle.pack4(want)
+        got = gpu_quantize(x, f, scale)
+        assert np.array_equal(got, want), (f, scale, int((got != want).sum()))
+
+
+def test_absmax_and_scale():
+    for n in (1, 5, 4096, 4097, 1310720, 5000001):
+        x = synth.activations((n,), 7 + n)
+        out = gpu_absmax_scale(dev(x), 448.0).cpu().numpy()
+        a = oracle.absmax(x)
+        assert out[0] == np.float32(a)
+        assert out[1] == np.float32(oracle.scale_from_absmax(a, 448.0))
+    z = gpu_absmax_scale(torch.zeros(1000, device=DEV), 448.0).cpu().numpy()
+    assert z[0] == 0.0 and z[1] == 1.0
+    e = gpu_absmax_scale(torch.zeros(0, device=DEV), 6.0).cpu().numpy()
+    assert e[0] == 0.0 and e[1] == 1.0
+    x = synth.activations((1001,), 3)
+    out = gpu_absmax_scale(dev(x)[1:], 6.0).cpu().numpy()       # unaligned start
+    assert out[0] == np.float32(oracle.absmax(x[1:]))
+
+
+@pytest.mark.parametrize("shape", [(1, 320, 64, 64), (2, 4, 9, 7), (3, 20, 5, 5), (1, 70, 1, 1), (2, 130, 16, 16)])
+def test_quantize_nhwc(shape):
+    f = synth.E4M3
+    x = synth.activations(shape, 41)
+    sx = oracle.scale_from_absmax(oracle.absmax(x), f[3])
+    Bn, Cc, H, W = shape
+    Cp = B.fpq_padded_channels(Cc)
+    codes = torch.full((Bn * H * W * Cp,), 0xEE, dtype=torch.uint8, device=DEV)
+    B.fpq_quantize_nhwc(dev(x), f, sx, None, codes)
+    torch.cuda.synchronize()
+    got = codes.cpu().numpy().reshape(Bn, H, W, Cp)
+    want = oracle.quantize(x, f, sx).transpose(0, 2, 3, 1)
+    assert np.array_equal(got[..., :Cc], want)
+    assert np.all(got[..., Cc:] == 0)
+
+
+# ------------------------------------------------------------------------------ weights
+
+@pytest.mark.parametrize("name", ["E2M1", "E4M3", "E1M2", "E3M0", "E3M4", "E2M1_b2", "E5M2"])
+@pytest.mark.parametrize("shape", [(320, 320), (7, 40, 3, 3), (33, 5, 1, 1), (4, 320, 3, 3)])
+def test_pack_weights_codes_and_scales(name, shape):
+    f = resolved(FORMATS[name])
+    w = synth.weights(shape, 4500)
+    w.reshape(-1)[::97] = 0.0
+    h = synth.rounding_mask(shape, 4750)
+    for mask in (h, None):
+        want_codes, want_sw = oracle.pack_weights(w, f, mask)
+        _, sw, codes = gpu_pack(w, f, mask)
+        assert np.array_equal(sw.cpu().numpy(), want_sw)
+        assert np.array_equal(codes, want_codes), int((codes != want_codes).sum())
+    # given scales, and on-grid / clipped weights under the mask (Eq. (12) literally)
+    sc = np.full(shape[0], 0.013, dtype=np.float32)
+    g = oracle.grid(f)
+    wg = (np.resize(np.concatenate([g, -g, [2 * f[3], -2 * f[3]]]), w.size).reshape(shape) * 0.013).astype(np.float32)
+    want_codes, _ = oracle.pack_weights(wg, f, h, sc)
+    _, sw, codes = gpu_pack(wg, f, h, sc)
+    assert np.array_equal(codes, want_codes) and np.array_equal(sw.cpu().numpy(), sc)
+
+
+# ------------------------------------------------------------------------------ linear layers
+
+def run_linear(x, w, h, fx, fw, acc, bias=None, fp32_in=False):
+    sx, xq, wq, sw = oracle_linear_inputs(x, w, h, fx, fw)
+    M, K = x.shape
+    N = w.shape[0]
+    packed, sw_t, codes = gpu_pack(w, fw, h)
+    assert np.array_equal(codes, wq)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+    bias_t = None if bias is None else dev(bias)
+    if fp32_in:
+        ws = torch.empty(max(1, B.fpq_gemm_workspace_size(M, N, K, 1)), dtype=torch.uint8, device=DEV)
+        B.fpq_gemm(dev(x), 1, fx, sx, None, packed, fw, sw_t, bias_t, y, M, N, K, acc, ws)
+    else:
+        B.fpq_gemm(dev(xq), 0, fx, sx, None, packed, fw, sw_t, bias_t, y, M, N, K, acc)
+    torch.cuda.synchronize()
+    return y.cpu().numpy(), (sx, xq, wq, sw)
+
+
+LIN_SHAPES = [(256, 320, 320), (1, 16, 1), (5, 48, 3), (77, 768, 320), (130, 128, 65), (64, 2880, 96), (200, 1280, 130)]
+PAIRS = [("E4M3", "E4M3"), ("E4M3", "E2M1"), ("E3M4", "E3M0"), ("E5M2", "E4M3"), ("E4M3", "E1M2"), ("E2M5", "E4M3_eq7"),
+         ("E4M3_b9", "E2M1_b2"), ("E4M3", "E5M2")]
+
+
+@pytest.mark.parametrize("M,K,N", LIN_SHAPES)
+@pytest.mark.parametrize("fxn,fwn", PAIRS)
+def test_linear_fp32_accumulate(M, K, N, fxn, fwn):
+    fx, fw = resolved(FORMATS[fxn]), resolved(FORMATS[fwn])
+    x = synth.activations((M, K), 1000 + M)
+    w = synth.weights((N, K), 1500 + N)
+    h = synth.rounding_mask((N, K), 1750 + N)
+    bias = np.linspace(-1, 1, N).astype(np.float32)
+    y, (sx, xq, wq, sw) = run_linear(x, w, h, fx, fw, B.FPQ_ACC_FP32, bias)
+    Y, T = oracle.gemm(xq, fx, sx, wq, fw, sw, bias)
+    check_close(y, Y, T, what="linear %s x %s %s" % (fxn, fwn, (M, K, N)))
+
+
+@pytest.mark.parametrize("M,K,N", LIN_SHAPES)
+@pytest.mark.parametrize("fxn,fwn", [("E4M3", "E4M3"), ("E4M3", "E2M1"), ("E5M2", "E4M3"), ("E4M3", "E5M2"),
+                                     ("E4M3_b9", "E2M1_b2")])
+def test_linear_fp8_mfma(M, K, N, fxn, fwn):
+    fx, fw = resolved(FORMATS[fxn]), resolved(FORMATS[fwn])
+    x = synth.activations((M, K), 1000 + M)
+    w = synth.weights((N, K), 1500 + N)
+    h = synth.rounding_mask((N, K), 1750 + N)
+    y, (sx, xq, wq, sw) = run_linear(x, w, h, fx, fw, B.FPQ_ACC_FP8_MFMA)
+    Y, T = oracle.gemm(xq, fx, sx, wq, fw, sw)
+    check_close(y, Y, T, rel=REL_FP8_MFMA, what="linear fp8-mfma %s x %s" % (fxn, fwn))
+
+
+def test_linear_fp32_input_equals_codes_input():
+    fx, fw = synth.E4M3, synth.E2M1
+    for (M, K, N) in [(256, 320, 320), (9, 40, 17), (300, 72, 64)]:
+        x = synth.activations((M, K), 5)
+        w = synth.weights((N, K), 6)
+        h = synth.rounding_mask((N, K), 7)
+        y1, (sx, xq, wq, sw) = run_linear(x, w, h, fx, fw, B.FPQ_ACC_FP32, fp32_in=True)
+        Y, T = oracle.gemm(xq, fx, sx, wq, fw, sw)
+        check_close(y1, Y, T, what="fp32-in %s" % ((M, K, N),))
+        if K % 16 == 0:
+            y0, _ = run_linear(x, w, h, fx, fw, B.FPQ_ACC_FP32)
+            assert np.array_equal(y0, y1)
+
+
+@pytest.mark.parametrize("acc", [B.FPQ_ACC_FP32, B.FPQ_ACC_FP8_MFMA])
+@pytest.mark.parametrize("fwn", ["E4M3", "E2M1"])
+def test_linear_exact_integers(acc, fwn):
+    """Small-integer operands at scale 1: every product and partial sum is an exact integer below 2^24, so
+    any summation order must reproduce the oracle with zero tolerance."""
+    fx, fw = synth.E4M3, resolved(FORMATS[fwn])
+    rng = np.random.default_rng(4)
+    M, K, N = 130, 384, 72
+    x = rng.choice(np.array([0, 1, 2, 3, 4, 5, 6, 7, 8, -1, -2, -3, -4, -6, -8], dtype=np.float32), (M, K))
+    w = rng.choice(np.array([0, 1, 2, 3, 4, 6, -1, -2, -3, -4, -6], dtype=np.float32), (N, K))
+    xq = oracle.quantize(x, fx, 1.0)
+    sc = np.ones(N, dtype=np.float32)
+    packed, sw_t, wq = gpu_pack(w, fw, None, sc)
+    y = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    B.fpq_gemm(dev(xq), 0, fx, 1.0, None, packed, fw, sw_t, None, y, M, N, K, acc)
+    torch.cuda.synchronize()
+    assert np.array_equal(y.cpu().numpy().astype(np.float64), x.astype(np.float64) @ w.astype(np.float64).T)
+    # doubling sx doubles the output exactly
+    y2 = torch.empty_like(y)
+    B.fpq_gemm(dev(xq), 0, fx, 2.0, None, packed, fw, sw_t, None, y2, M, N, K, acc)
+    torch.cuda.synchronize()
+    assert torch.equal(y2, 2 * y)
+
+
+@pytest.mark.parametrize("fxn,fwn", [("E4M3", "E4M3"), ("E4M3", "E2M1"), ("E3M4", "E3M0"), ("E5M2_eq7", "E1M2"),
+                                     ("E4M3_eq7", "E2M5"), ("E4M3_bneg", "E3M2")])
+def test_every_code_pair_decodes_exactly(fxn, fwn):
+    """X holds activation code i alone in row i, W holds weight code j alone in row j: Y[i, j] is the product
+    of the two decoded values, for all pairs of codes (single product: exact in fp32)."""
+    fx, fw = resolved(FORMATS[fxn]), resolved(FORMATS[fwn])
+    gx, gw = oracle.grid(fx), oracle.grid(fw)
+    cx = [c | s for s in (0, 1 << (fx[0] + fx[1])) for c in range(len(gx)) if gx[c] <= fx[3]]
+    cw = [c | s for s in (0, 1 << (fw[0] + fw[1])) for c in range(len(gw)) if gw[c] <= fw[3]]
+    K = 16
+    for pos in (0, 5, 15):
+        xq = np.zeros((len(cx), K), dtype=np.uint8)
+        xq[:, pos] = cx
+        wvals = oracle.dequantize(np.array(cw, dtype=np.uint8), fw, 1.0).astype(np.float32)
+        w = np.zeros((len(cw), K), dtype=np.float32)
+        w[:, pos] = wvals
+        sc = np.ones(len(cw), dtype=np.float32)
+        packed, sw_t, wq = gpu_pack(w, fw, None, sc)
+        assert np.array_equal(np.abs(oracle.dequantize(wq[:, pos], fw, 1.0)), np.abs(wvals.astype(np.float64)))
+        y = torch.empty((len(cx), len(cw)), dtype=torch.float32, device=DEV)
+        B.fpq_gemm(dev(xq), 0, fx, 1.0, None, packed, fw, sw_t, None, y, len(cx), len(cw), K, B.FPQ_ACC_FP32)
+        torch.cuda.synchronize()
+        want = np.outer(oracle.dequantize(np.array(cx, dtype=np.uint8), fx, 1.0), wvals.astype(np.float64))
+        assert np.array_equal(y.cpu().numpy().astype(np.float64), want.astype(np.float32).astype(np.float64))
+
+
+# ------------------------------------------------------------------------------ convolutions
+
+def run_conv(x, w, h, fx, fw, stride, pad, acc, bias=None, fp32_in=False):
+    sx = oracle.scale_from_absmax(oracle.absmax(x), fx[3])
+    xq = oracle.quantize(x, fx, sx)
+    wq, sw = oracle.pack_weights(w, fw, h)
+    Bn, Cin, H, W = x.shape
+    Cout, _, kh, kw = w.shape
+    Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+    packed, sw_t, codes = gpu_pack(w, fw, h)
+    assert np.array_equal(codes, wq)
+    y = torch.full((Bn, Cout, Ho, Wo), float("nan"), dtype=torch.float32, device=DEV)
+    bias_t = None if bias is None else dev(bias)
+    if fp32_in:
+        ws = torch.empty(B.fpq_conv2d_workspace_size(Bn, Cin, H, W, Cout, kh, kw, stride, pad, 1), dtype=torch.uint8,
+                         device=DEV)
+        B.fpq_conv2d(dev(x), 1, fx, sx, None, packed, fw, sw_t, bias_t, y, Bn, Cin, H, W, Cout, kh, kw, stride, pad,
+                     acc, ws)
+    else:
+        Cp = B.fpq_padded_channels(Cin)
+        codes_nhwc = torch.empty(Bn * H * W * Cp, dtype=torch.uint8, device=DEV)
+        B.fpq_quantize_nhwc(dev(x), fx, sx, None, codes_nhwc)
+        B.fpq_conv2d(codes_nhwc, 0, fx, sx, None, packed, fw, sw_t, bias_t, y, Bn, Cin, H, W, Cout, kh, kw, stride,
+                     pad, acc)
+    torch.cuda.synchronize()
+    return y.cpu().numpy(), (sx, xq, wq, sw)
+
+
+CONV_CASES = [  # B, Cin, H, W, Cout, k, stride, pad
+    (1, 16, 8, 8, 32, 3, 1, 1), (2, 4, 9, 7, 5, 3, 1, 1), (1, 20, 6, 6, 33, 3, 2, 1), (2, 32, 5, 5, 64, 1, 1, 0),
+    (1, 48, 12, 10, 130, 3, 1, 0), (3, 64, 7, 7, 4, 3, 1, 1), (1, 320, 16, 16, 96, 3, 1, 1), (2, 40, 8, 8, 40, 5, 1, 2),
+    (1, 16, 9, 9, 16, 3, 3, 1),
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+@pytest.mark.parametrize("fxn,fwn,acc", [("E4M3", "E4M3", 0), ("E4M3", "E2M1", 0), ("E3M4", "E3M0", 0),
+                                         ("E4M3", "E4M3", 1), ("E4M3", "E2M1", 1)])
+def test_conv_small_full_compare(case, fxn, fwn, acc):
+    Bn, Cin, H, W, Cout, k, stride, pad = case
+    fx, fw = resolved(FORMATS[fxn]), resolved(FORMATS[fwn])
+    x = synth.activations((Bn, Cin, H, W), 2000 + Cin)
+    w = synth.weights((Cout, Cin, k, k), 2500 + Cout)
+    h = synth.rounding_mask(w.shape, 2750 + Cout)
+    bias = np.linspace(-0.5, 0.5, Cout).astype(np.float32)
+    y, (sx, xq, wq, sw) = run_conv(x, w, h, fx, fw, stride, pad, acc, bias)
+    Y, T = oracle.conv2d(xq, fx, sx, wq, fw, sw, bias, stride=stride, pad=pad)
+    check_close(y, Y, T, rel=REL_FP8_MFMA if acc else 1e-5, what="conv %s %s x %s acc %d" % (case, fxn, fwn, acc))
+
+
+def test_conv_fp32_input_equals_codes_input():
+    fx, fw = synth.E4M3, synth.E4M3
+    x = synth.activations((2, 20, 9, 9), 1)
+    w = synth.weights((24, 20, 3, 3), 2)
+    h = synth.rounding_mask(w.shape, 3)
+    y0, _ = run_conv(x, w, h, fx, fw, 1, 1, 0)
+    y1, _ = run_conv(x, w, h, fx, fw, 1, 1, 0, fp32_in=True)
+    assert np.array_equal(y0, y1)
+
+
+def test_conv_one_hot_taps_exact():
+    """One non-zero input pixel and one non-zero weight tap: the output is a single 1 at the shifted position."""
+    fx = fw = synth.E4M3
+    Bn, Cin, H, W, Cout, k = 1, 16, 6, 5, 32, 3
+    for ci, r, t, hi, wi in [(0, 0, 0, 0, 0), (15, 2, 1, 5, 4), (3, 1, 2, 2, 0), (7, 0, 2, 0, 4), (9, 1, 1, 3, 3)]:
+        x = np.zeros((Bn, Cin, H, W), np.float32)
+        w = np.zeros((Cout, Cin, k, k), np.float32)
+        x[0, ci, hi, wi] = 1.0
+        w[17, ci, r, t] = 1.0
+        sc = np.ones(Cout, dtype=np.float32)
+        packed, sw_t, _ = gpu_pack(w, fw, None, sc)
+        codes = torch.empty(Bn * H * W * 16, dtype=torch.uint8, device=DEV)
+        B.fpq_quantize_nhwc(dev(x), fx, 1.0, None, codes)
+        y = torch.empty((Bn, Cout, H, W), dtype=torch.float32, device=DEV)
+        B.fpq_conv2d(codes, 0, fx, 1.0, None, packed, fw, sw_t, None, y, Bn, Cin, H, W, Cout, k, k, 1, 1, 0)
+        torch.cuda.synchronize()
+        want = np.zeros((Bn, Cout, H, W), np.float32)
+        ho, wo = hi + 1 - r, wi + 1 - t
+        if 0 <= ho < H and 0 <= wo < W:
+            want[0, 17, ho, wo] = 1.0
+        assert np.array_equal(y.cpu().numpy(), want)
