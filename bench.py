@@ -1,0 +1,263 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized-layer hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input: for every layer of the
+workload, absmax calibration of the fp32 activation (device-resident scale), activation quantize
+to E4M3 codes, and the quantized linear / conv layer on pre-packed weights -- once with E4M3
+weights (W8A8) and once with E2M1 weights (W4A8).  Weight packing is the offline step and is done
+before the timed region; inputs are resident in HBM.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg4|cfg3|cfg2|cfg1]
+                    [--acc fp32|fp8mfma] [--no-cpu-baseline]
+
+Prints ONE JSON line: metric / value (whole-step TFLOP/s), the roofline object of the dominant
+kernel (live hipEvent timing of every GEMM launch, on the stream the launches use), the CPU oracle
+baseline timed on the host cores, the quantize kernel's bandwidth, and the same step through the
+FP8-MFMA accumulate mode for reference.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_FP8_TFLOPS = 5000.0    # MI355X dense fp8 MFMA (also the rate of fp8 x fp4)
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg5")
+    ap.add_argument("--acc", default="fp32", choices=["fp32", "fp8mfma"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the quantize-bandwidth probe and the other acc mode")
+    return ap.parse_args()
+
+
+WORKLOAD_NAMES = {
+    "cfg1": "configs[0]: single linear layer 256x320x320, W8A8 + W4A8",
+    "cfg2": "configs[1]: 3x3 conv 320->320 on 64x64, batch 1 (M=4096 K=2880 N=320), W8A8 + W4A8",
+    "cfg3": "configs[2]: transformer-block projections (QKV, GEGLU, FF-out, cross-attn K/V), W8A8 + W4A8",
+    "cfg4": "configs[3]: deep-stage 3x3 conv 1280->1280 on 16x16, batch 8 (M=2048 K=11520 N=1280), W8A8 + W4A8",
+    "cfg5": "configs[4]: full SD-like U-Net denoising-step layer set (250 conv/linear layers, batch 8, 64x64 latent), "
+            "W8A8 (E4M3 weights) then W4A8 (E2M1 weights)",
+}
+
+
+class LayerState:
+    pass
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus %d is not supported (no multi-GPU path exists)"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2408_06995_amd import binding as B
+    from paper_2408_06995_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.lib()   # fail loudly if the HIP library is missing
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = int(args.workload[3:])
+    layers = synth.unet_layers() if cfg == 5 else synth.config_layers(cfg)
+    FX, FW8, FW4 = synth.E4M3, synth.E4M3, synth.E2M1
+    acc = B.FPQ_ACC_FP32 if args.acc == "fp32" else B.FPQ_ACC_FP8_MFMA
+
+    # ---- set-up (untimed): inputs resident in HBM, weights quantized and packed offline
+    states = []
+    max_y = 0
+    max_ws = 0
+    for li, L in enumerate(layers):
+        s = LayerState()
+        s.L = L
+        sx_seed, sw_seed, sh_seed = synth.seeds(cfg, li)
+        if L.kind == "conv":
+            s.x = synth.activations_torch((L.B, L.Cin, L.H, L.W), sx_seed, dev)
+            wshape = (L.Cout, L.Cin, L.k, L.k)
+            ws = B.fpq_conv2d_workspace_size(L.B, L.Cin, L.H, L.W, L.Cout, L.k, L.k, L.stride, L.pad, 1)
+        else:
+            s.x = synth.activations_torch((L.M, L.K), sx_seed, dev)
+            wshape = (L.N, L.K)
+            ws = B.fpq_gemm_workspace_size(L.M, L.N, L.K, 1)
+        w = synth.weights_torch(wshape, sw_seed, dev)
+        h = synth.rounding_mask_torch(wshape, sh_seed, dev)
+        kk = L.k if L.kind == "conv" else 1
+        s.packed = {}
+        s.sw = {}
+        for tag, fw, mask in (("w8", FW8, None), ("w4", FW4, h)):   # rounding mask only for FP4 (Section V-B)
+            p = torch.empty(B.fpq_packed_size(L.N, L.Cin, kk, kk, fw), dtype=torch.uint8, device=dev)
+            sw = torch.empty(L.N, dtype=torch.float32, device=dev)
+            B.fpq_pack_weights(w, fw, None, mask, p, sw, None)
+            s.packed[tag], s.sw[tag] = p, sw
+        del w, h
+        s.scale = torch.empty(2, dtype=torch.float32, device=dev)   # [absmax, scale]
+        max_y = max(max_y, L.M * L.N)
+        max_ws = max(max_ws, ws)
+        states.append(s)
+    torch.cuda.synchronize()
+    y = torch.empty(max_y, dtype=torch.float32, device=dev)
+    ws_buf = torch.empty(max(max_ws, 256), dtype=torch.uint8, device=dev)
+    amax_ws = torch.empty(1024, dtype=torch.float32, device=dev)
+
+    def run_layer(s, tag, fw, acc_mode):
+        L = s.L
+        B.fpq_absmax(s.x, FX[3], s.scale[0:1], s.scale[1:2], amax_ws)
+        if L.kind == "conv":
+            B.fpq_conv2d(s.x, 1, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, y, L.B, L.Cin, L.H, L.W,
+                         L.Cout, L.k, L.k, L.stride, L.pad, acc_mode, ws_buf)
+        else:
+            B.fpq_gemm(s.x, 1, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, y, L.M, L.N, L.K, acc_mode,
+                       ws_buf)
+
+    def step(acc_mode):
+        for tag, fw in (("w8", FW8), ("w4", FW4)):
+            for s in states:
+                run_layer(s, tag, fw, acc_mode)
+
+    flops_step = 2 * sum(synth.flops(L) for L in layers)
+
+    def timed(acc_mode, steps, warmup):
+        for _ in range(warmup):
+            step(acc_mode)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step(acc_mode)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    sec = timed(acc, args.steps, args.warmup)
+
+    # ---- per-kernel breakdown: hipEvents around every GEMM launch (quantize done separately so that the
+    # events bracket the GEMM kernel alone), on torch's current stream = the stream the library launches on
+    def gemm_breakdown(acc_mode, reps=3):
+        tot_ms, tot_fl, nlaunch = 0.0, 0.0, 0
+        per_layer = {}
+        for tag, fw in (("w8", FW8), ("w4", FW4)):
+            for s in states:
+                L = s.L
+                B.fpq_absmax(s.x, FX[3], s.scale[0:1], s.scale[1:2], amax_ws)
+                if L.kind == "conv":
+                    B.fpq_quantize_nhwc(s.x, FX, 0.0, s.scale[1:2], ws_buf)
+                elif B.fpq_padded_channels(L.K) == L.K:
+                    B.fpq_quantize(s.x, FX, 0.0, s.scale[1:2], ws_buf)
+                else:
+                    continue   # rows need padding: only reachable through the fused entry point
+                best = None
+                for _ in range(reps):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    if L.kind == "conv":
+                        B.fpq_conv2d(ws_buf, 0, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, y, L.B,
+                                     L.Cin, L.H, L.W, L.Cout, L.k, L.k, L.stride, L.pad, acc_mode)
+                    else:
+                        B.fpq_gemm(ws_buf, 0, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, y, L.M, L.N,
+                                   L.K, acc_mode)
+                    e1.record()
+                    e1.synchronize()
+                    ms = e0.elapsed_time(e1)
+                    best = ms if best is None else best + ms
+                ms = best / reps
+                tot_ms += ms
+                tot_fl += synth.flops(L)
+                nlaunch += 1
+                per_layer[(tag, L.name)] = ms
+        return tot_ms, tot_fl, nlaunch, per_layer
+
+    g_ms, g_fl, g_n, per_layer = gemm_breakdown(acc)
+    peak = PEAK_BF16_TFLOPS if acc == B.FPQ_ACC_FP32 else PEAK_FP8_TFLOPS
+    achieved = g_fl / (g_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "fpq::gemm_kernel (all launches of one step)", "achieved": round(achieved, 2),
+                "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
+                "launches": g_n, "avg_launch_us": round(g_ms * 1e3 / g_n, 2),
+                "gemm_ms_per_step": round(g_ms, 4)}
+
+    out = {
+        "metric": "W8A8+W4A8 GEMM/conv TFLOP/s incl. absmax + activation quantize (whole step)",
+        "value": round(flops_step / sec / 1e12, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "fp8/fp4 codes -> bf16 MFMA, fp32 accumulate" if acc == B.FPQ_ACC_FP32 else "fp8/fp4 MFMA",
+        "data": "synthetic",
+        "config": {"workload": WORKLOAD_NAMES[args.workload], "layers": len(layers), "flop_per_step": flops_step,
+                   "acc_mode": args.acc},
+        "roofline": roofline,
+    }
+
+    if not args.no_extras:
+        # the other accumulate mode, same step
+        other = B.FPQ_ACC_FP8_MFMA if acc == B.FPQ_ACC_FP32 else B.FPQ_ACC_FP32
+        sec_o = timed(other, max(2, args.steps // 2), 1)
+        o_ms, o_fl, o_n, _ = gemm_breakdown(other, reps=2)
+        peak_o = PEAK_FP8_TFLOPS if other == B.FPQ_ACC_FP8_MFMA else PEAK_BF16_TFLOPS
+        out["other_acc_mode"] = {"acc_mode": "fp8mfma" if other == B.FPQ_ACC_FP8_MFMA else "fp32",
+                                 "value": round(flops_step / sec_o / 1e12, 3), "unit": "TFLOP/s",
+                                 "gemm_achieved": round(o_fl / (o_ms * 1e-3) / 1e12, 2), "peak": peak_o,
+                                 "frac": round(o_fl / (o_ms * 1e-3) / 1e12 / peak_o, 4)}
+        # activation-quantize bandwidth: 64 Mi elements per launch, rotating over 8 buffers (2.7 GB) so that the
+        # last-level cache cannot serve the reads; algorithmic bytes = 5 per element (4 read + 1 written)
+        n = 64 << 20
+        bufs = [torch.randn(n, device=dev) for _ in range(8)]
+        codes = [torch.empty(n, dtype=torch.uint8, device=dev) for _ in range(2)]
+        sc = torch.tensor([0.01], device=dev)
+        for i in range(4):
+            B.fpq_quantize(bufs[i], FX, 0.0, sc, codes[i & 1])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        reps = 32
+        for i in range(reps):
+            B.fpq_quantize(bufs[i & 7], FX, 0.0, sc, codes[i & 1])
+        e1.record()
+        e1.synchronize()
+        q_gbs = 5.0 * n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        am = torch.empty(2, device=dev)
+        e0.record()
+        for i in range(reps):
+            B.fpq_absmax(bufs[i & 7], 448.0, am[0:1], am[1:2], amax_ws)
+        e1.record()
+        e1.synchronize()
+        a_gbs = 4.0 * n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        out["quantize"] = {"elements": n, "GB/s": round(q_gbs, 1), "frac_of_hbm_peak": round(q_gbs / PEAK_HBM_GBS, 4),
+                           "absmax_GB/s": round(a_gbs, 1), "absmax_frac": round(a_gbs / PEAK_HBM_GBS, 4)}
+        del bufs, codes
+
+    if not args.no_cpu_baseline:
+        import oracle
+        # bounded sample of the same kind of work: the config-2 conv layer (7.55 GFLOP) and a 1/4 row sample of
+        # the config-4 conv (15.1 GFLOP), W8A8, through the oracle as it stands, on the host cores
+        t_cpu, fl_cpu = 0.0, 0.0
+        for (shape, wshape, npix) in (((1, 320, 64, 64), (320, 320, 3, 3), None), ((8, 1280, 16, 16), (1280, 1280, 3, 3), 512)):
+            x = synth.activations(shape, 2000)
+            w = synth.weights(wshape, 2500)
+            t0 = time.perf_counter()
+            sx = oracle.scale_from_absmax(oracle.absmax(x), FX[3])
+            xq = oracle.quantize(x, FX, sx)
+            wq, sw = oracle.pack_weights(w, FW8)
+            M = shape[0] * shape[2] * shape[3]
+            pix = None if npix is None else np.arange(0, M, M // npix)
+            oracle.conv2d(xq, FX, sx, wq, FW8, sw, stride=1, pad=1, pix=pix)
+            t_cpu += time.perf_counter() - t0
+            fl_cpu += 2.0 * (M if pix is None else len(pix)) * wshape[0] * wshape[1] * 9
+        out["cpu_baseline"] = {"value": round(fl_cpu / t_cpu / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+                               "kind": "oracle",
+                               "sample": "oracle quantize + pack + conv2d: config-2 conv in full and 512 of 2048 output "
+                                         "pixels of the config-4 conv (%.1f GFLOP, %.1f s)" % (fl_cpu / 1e9, t_cpu)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
