@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--acc", default="fp32", choices=["fp32", "fp8mfma"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the quantize-bandwidth probe and the other acc mode")
+    ap.add_argument("--per-layer", default=None, help="write a per-layer GEMM timing table to this file")
     return ap.parse_args()
 
 
@@ -81,6 +82,7 @@ def main():
     states = []
     max_y = 0
     max_ws = 0
+    max_part = 0
     for li, L in enumerate(layers):
         s = LayerState()
         s.L = L
@@ -107,11 +109,16 @@ def main():
         s.scale = torch.empty(2, dtype=torch.float32, device=dev)   # [absmax, scale]
         max_y = max(max_y, L.M * L.N)
         max_ws = max(max_ws, ws)
+        if L.kind == "conv":
+            max_part = max(max_part, B.fpq_conv2d_workspace_size(L.B, L.Cin, L.H, L.W, L.Cout, L.k, L.k, L.stride, L.pad, 0))
+        else:
+            max_part = max(max_part, B.fpq_gemm_workspace_size(L.M, L.N, L.K, 0))
         states.append(s)
     torch.cuda.synchronize()
     y = torch.empty(max_y, dtype=torch.float32, device=dev)
     ws_buf = torch.empty(max(max_ws, 256), dtype=torch.uint8, device=dev)
     amax_ws = torch.empty(1024, dtype=torch.float32, device=dev)
+    part_buf = torch.empty(max(max_part, 256), dtype=torch.uint8, device=dev)   # split-K partial sums (codes-input calls)
 
     def run_layer(s, tag, fw, acc_mode):
         L = s.L
@@ -163,10 +170,10 @@ def main():
                     e0.record()
                     if L.kind == "conv":
                         B.fpq_conv2d(ws_buf, 0, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, y, L.B,
-                                     L.Cin, L.H, L.W, L.Cout, L.k, L.k, L.stride, L.pad, acc_mode)
+                                     L.Cin, L.H, L.W, L.Cout, L.k, L.k, L.stride, L.pad, acc_mode, part_buf)
                     else:
                         B.fpq_gemm(ws_buf, 0, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, y, L.M, L.N,
-                                   L.K, acc_mode)
+                                   L.K, acc_mode, part_buf)
                     e1.record()
                     e1.synchronize()
                     ms = e0.elapsed_time(e1)
@@ -179,6 +186,13 @@ def main():
         return tot_ms, tot_fl, nlaunch, per_layer
 
     g_ms, g_fl, g_n, per_layer = gemm_breakdown(acc)
+    if args.per_layer:
+        with open(args.per_layer, "w") as fh:
+            fh.write("# weights layer kind M K N k stride GFLOP us TFLOP/s\n")
+            for (tag, name), ms in per_layer.items():
+                L = [l for l in layers if l.name == name][0]
+                fh.write("%s %s %s %d %d %d %d %d %.3f %.2f %.1f\n" % (tag, name, L.kind, L.M, L.K, L.N, L.k, L.stride,
+                         synth.flops(L) / 1e9, ms * 1e3, synth.flops(L) / (ms * 1e-3) / 1e12))
     peak = PEAK_BF16_TFLOPS if acc == B.FPQ_ACC_FP32 else PEAK_FP8_TFLOPS
     achieved = g_fl / (g_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "fpq::gemm_kernel (all launches of one step)", "achieved": round(achieved, 2),

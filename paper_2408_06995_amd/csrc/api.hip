@@ -248,17 +248,19 @@ int fpq_pack_weights(const float* w, int64_t N, int64_t Cin, int kh, int kw, fpq
 
 size_t fpq_gemm_workspace_size(int64_t M, int64_t N, int64_t K, int x_is_fp32)
 {
-    (void)N;
-    if (M <= 0 || K <= 0 || !x_is_fp32) return 0;
-    return align_up((size_t)M * (size_t)padded_channels(K), 256);
+    if (M <= 0 || K <= 0 || N <= 0) return 0;
+    size_t codes = x_is_fp32 ? align_up((size_t)M * (size_t)padded_channels(K), 256) : 0;
+    return codes + split_workspace_bytes(plan_gemm(M, N, padded_k(K, 1)), M, N);
 }
 
 size_t fpq_conv2d_workspace_size(int64_t B, int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh, int kw,
                                  int stride, int pad, int x_is_fp32)
 {
-    (void)Cout; (void)kh; (void)kw; (void)stride; (void)pad;
-    if (B <= 0 || Cin <= 0 || H <= 0 || W <= 0 || !x_is_fp32) return 0;
-    return align_up((size_t)B * H * W * (size_t)padded_channels(Cin), 256);
+    if (B <= 0 || Cin <= 0 || H <= 0 || W <= 0 || Cout <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0) return 0;
+    if (H + 2 * pad < kh || W + 2 * pad < kw) return 0;
+    const int64_t Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
+    size_t codes = x_is_fp32 ? align_up((size_t)B * H * W * (size_t)padded_channels(Cin), 256) : 0;
+    return codes + split_workspace_bytes(plan_gemm(B * Ho * Wo, Cout, padded_k(Cin, (int64_t)kh * kw)), B * Ho * Wo, Cout);
 }
 
 static int run_layer(const void* x, int x_is_fp32, fpq_format_t fx, float sx, const float* sx_dev,
@@ -290,11 +292,16 @@ static int run_layer(const void* x, int x_is_fp32, fpq_format_t fx, float sx, co
     if ((reinterpret_cast<uintptr_t>(packed_w) & 15) || (reinterpret_cast<uintptr_t>(y) & 3)) return FPQ_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint8_t* xcodes;
+    // workspace = [activation codes when the input is fp32][split-K partial results]; a caller that passes
+    // codes and no (or too small a) workspace gets the unsplit kernel
+    GemmPlan plan = plan_gemm(M, Cout, padded_k(Cin, (int64_t)kh * kw));
+    const size_t codes_bytes = x_is_fp32 ? align_up((size_t)B * H * W * (size_t)Cp, 256) : 0;
+    const size_t part_bytes = split_workspace_bytes(plan, M, Cout);
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255)) return FPQ_ERR_ALIGN;
+    if (x_is_fp32 && (!workspace || workspace_bytes < codes_bytes + part_bytes)) return FPQ_ERR_WORKSPACE;
+    if (!x_is_fp32 && (!workspace || workspace_bytes < part_bytes)) plan.splits = 1;
+    float* partial = plan.splits > 1 ? reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + codes_bytes) : nullptr;
     if (x_is_fp32) {
-        size_t need = conv_out ? fpq_conv2d_workspace_size(B, Cin, H, W, Cout, kh, kw, stride, pad, 1)
-                               : fpq_gemm_workspace_size(M, Cout, Cin, 1);
-        if (!workspace || workspace_bytes < need) return FPQ_ERR_WORKSPACE;
-        if (reinterpret_cast<uintptr_t>(workspace) & 255) return FPQ_ERR_ALIGN;
         if (reinterpret_cast<uintptr_t>(x) & 3) return FPQ_ERR_ALIGN;
         uint8_t* buf = static_cast<uint8_t*>(workspace);
         if (conv_out) {
@@ -334,6 +341,20 @@ static int run_layer(const void* x, int x_is_fp32, fpq_format_t fx, float sx, co
     a.xe = fx.ebits; a.xm = fx.mbits; a.xb = fx.bias;
     a.we = fw.ebits; a.wm = fw.mbits; a.wb = fw.bias;
     a.acc_mode = acc_mode;
+    a.partial = partial;
+    a.splits = plan.splits;
+    a.tile = plan.tile;
+    a.x_bytes = (uint32_t)(B * H * W * Cp);
+    {
+        const int64_t wrow = is_four_bit(fw) ? a.Kpad / 2 : a.Kpad;
+        if (wrow * Cout >= (int64_t)1 << 31) return FPQ_ERR_SHAPE;
+        a.w_bytes = (uint32_t)(wrow * Cout);
+    }
+    if (!gemm_dma_applicable(a)) {   // operand pairing only the generic kernels serve
+        a.tile = TILE_GENERIC;
+        a.splits = 1;
+        a.partial = nullptr;
+    }
     return launch_gemm(a, s);
 }
 

@@ -67,7 +67,57 @@ struct GemmArgs {
     int xe, xm, xb;         // activation format (for the generic decode)
     int we, wm, wb;         // weight format
     int acc_mode;
+    uint32_t x_bytes;       // size of the activation code buffer (bound of the buffer loads)
+    uint32_t w_bytes;       // size of the packed weight rows
+    float* partial;         // split-K: splits x [M*N] partial results (null: no split)
+    int splits;             // number of K slices (>= 1)
+    int tile;               // GemmTile chosen by plan_gemm
 };
+
+// Kernel family / tile for a problem, and how many K slices share an output tile.
+enum GemmTile : int {
+    TILE_GENERIC = 0,    // register-staged 128x128 / 64x64 kernels: any shape
+    TILE_256x160_S3 = 1, // LDS-DMA kernel, three stages: deep K
+    TILE_128x160_S2 = 2  // LDS-DMA kernel, two stages, two workgroups per compute unit: short K
+};
+struct GemmPlan {
+    int tile;
+    int splits;
+};
+
+// The large-tile kernels need N to be a multiple of 160 (every U-Net width, a multiple of 320, is)
+// and at least one full tile of rows.  Short K (the layer is bound by writing its fp32 output) takes
+// the small tile so that two workgroups per compute unit overlap their store and load phases.  When
+// the tile grid alone would leave compute units idle, K is cut into slices: aim at one workgroup per
+// compute unit, keep at least 4 K steps per slice and at most 256 MB of partial results.
+static inline GemmPlan plan_gemm(int64_t M, int64_t N, int64_t Kpad)
+{
+    GemmPlan p{TILE_GENERIC, 1};
+    if (N % 160 != 0 || M < 256) return p;
+    const int64_t nk = Kpad / 128;
+#if defined(FPQ_EXP) && FPQ_EXP == 8
+    p.tile = TILE_256x160_S3;
+    const int64_t tiles = ((M + 255) / 256) * (N / 160);
+    const int64_t want = 256;
+#else
+    p.tile = TILE_128x160_S2;
+    const int64_t tiles = ((M + 127) / 128) * (N / 160);
+    const int64_t want = 512;
+#endif
+    if (tiles < want * 3 / 4) {
+        int64_t s = (want + tiles - 1) / tiles;
+        if (s > nk / 4) s = nk / 4;
+        if (s > 16) s = 16;
+        while (s > 1 && s * M * N * 4 > ((int64_t)256 << 20)) --s;
+        if (s < 1) s = 1;
+        p.splits = (int)s;
+    }
+    return p;
+}
+static inline size_t split_workspace_bytes(const GemmPlan& p, int64_t M, int64_t N)
+{
+    return p.splits > 1 ? (size_t)p.splits * (size_t)M * (size_t)N * sizeof(float) : 0;
+}
 
 int launch_absmax(const float* x, size_t n, float maxval, float* absmax_out, float* scale_out, float* partial,
                   hipStream_t st);
@@ -80,5 +130,7 @@ int launch_pack_weights(const float* w, int64_t N, int64_t Cin, int taps, const 
                         const float* scale_in, const uint8_t* mask, uint8_t* packed_rows, float* scale_out,
                         uint8_t* codes_out, hipStream_t st);
 int launch_gemm(const GemmArgs& a, hipStream_t st);
+bool gemm_dma_applicable(const GemmArgs& a);
+int launch_gemm_dma(const GemmArgs& a, hipStream_t st);
 
 }  // namespace fpq

@@ -1,0 +1,605 @@
+// Quantized linear / convolution layer on ExMy codes for gfx950: the large-tile kernel.
+//
+// A workgroup of four wavefronts owns a BX x BW tile (BX activation rows, BW weight rows; the
+// wavefronts split the activation rows) and walks its K range in steps of 128 codes through a
+// three-stage LDS ring.  Codes travel global memory -> LDS without touching registers:
+// buffer_load_dwordx4 ... lds writes 64 lanes x 16 bytes to consecutive LDS addresses, and a lane
+// whose element does not exist (row beyond M or N, padding pixel of the convolution, K beyond the
+// real length) gives an offset outside the buffer, for which the hardware delivers zeros = code 0.
+// The xor swizzle of the LDS tile (see lds_off) is applied on the global side, by choosing which
+// 16-byte chunk a lane fetches.  Loads for step k+2 are issued while step k is computed; one
+// s_waitcnt vmcnt + s_barrier per step orders them (the counts are spelled out at the loop).
+//
+// The kernel is persistent: the grid has at most one workgroup per compute unit and each workgroup
+// walks a strided list of work items (output tile, K slice), so that the loads of the next item are
+// already in flight while the current item's results are scaled and stored.
+//
+// Split-K: the K steps of an output tile can be cut into slices; slice s writes its scaled partial
+// sums to partial[s] and a second kernel adds the slices into y.
+#include "gemm_common.h"
+
+namespace fpq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// One wave-wide 16-byte-per-lane load from a buffer straight into LDS: lane i's bytes land at
+// lds_addr + 16 i; a lane whose voff is not below the buffer's size gets zeros.  Written as inline
+// assembly so that the compiler's wait-count insertion does not see an LDS write here (it would
+// drain every outstanding load before each following LDS read); the waits are placed by hand in
+// the main loop.  m0 carries the LDS base; nothing else in these kernels uses m0.
+__device__ __forceinline__ void dma16(v4i rsrc, unsigned voff, unsigned lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rsrc)
+                 : "memory");
+}
+
+// Raw buffer descriptor: base address, no stride, size in bytes, 32-bit untyped data.
+__device__ __forceinline__ v4i make_rsrc(const void* base, unsigned bytes)
+{
+    const unsigned long long b = reinterpret_cast<unsigned long long>(base);
+    v4i r;
+    r.x = (int)(unsigned)b;
+    r.y = (int)((unsigned)(b >> 32) & 0xffffu);
+    r.z = (int)bytes;
+    r.w = 0x00020000;
+    return r;
+}
+
+// s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
+// expcnt 6:4 and lgkmcnt 11:8 left at their maxima).
+constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+
+template <int BX, int BW, int NSTAGE, int XKIND, int WKIND, int ACC, bool CONV>
+__global__ __launch_bounds__(256, (BX <= 128 ? 2 : 1)) void gemm_dma_kernel(const GemmArgs a)
+{
+    constexpr bool W4 = kind_is_4bit(WKIND);
+    constexpr int XROWB = 128;
+    constexpr int WROWB = W4 ? 64 : 128;
+    constexpr int XTILE = BX * XROWB;
+    constexpr int WTILE = (BW * WROWB + 4095) / 4096 * 4096;   // whole 1-KB loads for each of 4 waves
+    constexpr int STAGE = XTILE + WTILE;
+    constexpr int XLD = XTILE / 4096;          // loads per wave and stage, activations
+    constexpr int WLD = WTILE / 4096;          // loads per wave and stage, weights
+    constexpr int LOADS = XLD + WLD;
+    constexpr int XRPL = 8;                    // tile rows covered by one wave-wide load (128-byte rows)
+    constexpr int WRPL = 1024 / WROWB;
+    static_assert(XTILE % 4096 == 0, "activation tile must split evenly over the waves");
+    // P = operand indexed by the accumulator registers, Q = operand indexed by the lane.
+    // P = activations, Q = weights (see the epilogue for what that means for the stores).
+    constexpr bool P_IS_W = false;
+    constexpr int TX = BX / 4;                 // activation rows per wave
+    constexpr int TP = P_IS_W ? BW : TX, TQ = P_IS_W ? TX : BW;
+    constexpr int MI = TP / 32, NI = TQ / 32;
+    static_assert(BW % 32 == 0 && TX % 32 == 0, "tile shape");
+    constexpr int PKIND = P_IS_W ? WKIND : XKIND, QKIND = P_IS_W ? XKIND : WKIND;
+    constexpr int PROWB = P_IS_W ? WROWB : XROWB, QROWB = P_IS_W ? XROWB : WROWB;
+    constexpr bool P4 = kind_is_4bit(PKIND), Q4 = kind_is_4bit(QKIND);
+    constexpr int PFMT = mfma_fmt(PKIND), QFMT = mfma_fmt(QKIND);
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
+    const int l32 = lane & 31;
+    const int g = lane >> 5;
+
+    // Work items = (output tile, K slice), tile-major.  Workgroup ids go round-robin over the 8 XCDs;
+    // regroup them so that each XCD (one L2) holds a contiguous run of logical ids, hence of items,
+    // which share activation rows.  Logical workgroup q takes items q, q + G, q + 2G, ...
+    const int tiles_w = (a.N + BW - 1) / BW;
+    const int tiles_x = (a.M + BX - 1) / BX;
+    const int nitems = tiles_w * tiles_x * a.splits;
+    const int G = gridDim.x;
+    int q = blockIdx.x;
+    {
+        const int per = G >> 3;
+        if (q < (per << 3)) q = (q & 7) * per + (q >> 3);
+    }
+    const int nk_all = a.Kpad / 128;
+
+    // ---- load bookkeeping
+    const v4i xrsrc = make_rsrc(a.x, a.x_bytes);
+    const v4i wrsrc = make_rsrc(a.wrows, a.w_bytes);
+    const unsigned lds0 = (unsigned)(size_t)((__attribute__((address_space(3))) void*)smem);
+    constexpr unsigned OOB = 0x80000000u;
+
+    // Activations: load i of this wave covers tile rows (4 i + wave) * 8 .. + 8; lane p holds row p / 8 of
+    // them and LDS chunk p % 8, i.e. logical chunk (p % 8) ^ swizzle(row).  The swizzle term is the same
+    // for all i, so a lane fetches the same K offset within every row it serves.
+    const int xrl = lane >> 3;
+    const int xc = (lane & 7) ^ ((wave * 4 + (lane >> 4)) & 7);
+    unsigned xbase[XLD];                       // byte offset of the row's tap (0,0), channel 0 (wraps below zero for halo rows)
+    unsigned xmask[XLD];                       // bit t: tap t of this row exists (inside the image, row < M); linear: bit 0
+    int x_k = 0, x_ci = 0, x_kh = 0, x_kw = 0, x_tap = 0;   // K position of this lane's chunk
+    int x_sel = 31;                            // x_tap, or 31 (a bit that is never set) once past the end of K
+    unsigned x_delta = 0;                      // byte offset of (tap, channel) relative to xbase
+    // Weights: same scheme on rows of WROWB bytes.
+    const int wrl = W4 ? (lane >> 2) : (lane >> 3);
+    const int wc = W4 ? ((lane & 3) ^ ((lane >> 4) & 3)) : ((lane & 7) ^ ((wave * 4 + (lane >> 4)) & 7));
+    const unsigned wrow_bytes = W4 ? (unsigned)a.Kpad / 2 : (unsigned)a.Kpad;
+    unsigned wbase[WLD];
+
+    bool ihas = true;                          // false once this workgroup has no more loads to issue
+    auto x_refresh = [&]() {
+        x_sel = (ihas && x_k < a.Kreal) ? x_tap : 31;
+        x_delta = CONV ? (unsigned)((x_kh * a.W + x_kw) * a.Cp + x_ci) : (unsigned)x_k;
+    };
+
+    int i_item = q;                            // item whose loads are being issued
+    int i_rem = 0;                             // K steps of it not yet issued
+    auto issue_setup = [&]() {
+        const int tile = i_item / a.splits, sl = i_item - tile * a.splits;
+        const int tx = tile / tiles_w, tw = tile - tx * tiles_w;
+        const int m0 = tx * BX, n0 = tw * BW;
+        const int kt0 = (int)((long)nk_all * sl / a.splits);
+        i_rem = (int)((long)nk_all * (sl + 1) / a.splits) - kt0;
+        int hi0[XLD], wi0[XLD];
+#pragma unroll
+        for (int i = 0; i < XLD; ++i) {
+            const int m = m0 + (4 * i + wave) * XRPL + xrl;
+            const bool rowok = m < a.M;
+            hi0[i] = wi0[i] = 0;
+            if (CONV) {
+                const int hw = a.Ho * a.Wo;
+                const int bi = m / hw;
+                const int rem = m - bi * hw;
+                const int ho = rem / a.Wo, wo = rem - ho * a.Wo;
+                hi0[i] = ho * a.stride - a.pad;
+                wi0[i] = wo * a.stride - a.pad;
+                xbase[i] = (unsigned)(((bi * a.H + hi0[i]) * a.W + wi0[i]) * a.Cp);
+                xmask[i] = rowok ? 0u : 0x80000000u;   // bit 31 marks a row to skip while the taps are collected
+            } else {
+                xbase[i] = (unsigned)m * (unsigned)a.Cp;
+                xmask[i] = rowok ? 1u : 0u;
+            }
+        }
+        if (CONV) {
+            int r = 0, c = 0;
+            const int ntaps = a.kh * a.kw;
+            for (int t = 0; t < ntaps; ++t) {
+#pragma unroll
+                for (int i = 0; i < XLD; ++i) {
+                    const bool ok = ((unsigned)(hi0[i] + r) < (unsigned)a.H) & ((unsigned)(wi0[i] + c) < (unsigned)a.W);
+                    xmask[i] |= ok ? (1u << t) : 0u;
+                }
+                if (++c == a.kw) { c = 0; ++r; }
+            }
+#pragma unroll
+            for (int i = 0; i < XLD; ++i) xmask[i] = (xmask[i] & 0x80000000u) ? 0u : xmask[i];
+        }
+        x_k = kt0 * 128 + xc * 16;
+        x_ci = x_k;
+        x_kh = x_kw = x_tap = 0;
+        if (CONV) {
+            x_tap = x_k / a.Cp;
+            x_ci = x_k - x_tap * a.Cp;
+            x_kh = x_tap / a.kw;
+            x_kw = x_tap - x_kh * a.kw;
+        }
+        x_refresh();
+#pragma unroll
+        for (int i = 0; i < WLD; ++i) {
+            const int row = (4 * i + wave) * WRPL + wrl;
+            const int n = n0 + row;
+            wbase[i] = (row < BW && n < a.N) ? (unsigned)n * wrow_bytes + (unsigned)kt0 * WROWB + wc * 16 : OOB;
+        }
+    };
+
+    // Load number idx of a step (0 .. LOADS-1) into ring slot `stage`: four VALU instructions and the load.
+    auto issue_one = [&](int idx, int stage) {
+        const unsigned xs = lds0 + stage * STAGE;
+        if (idx < XLD) {
+            const unsigned off = ((xmask[idx] >> x_sel) & 1u) ? xbase[idx] + x_delta : OOB;
+            dma16(xrsrc, off, xs + (4 * idx + wave) * 1024);
+        } else {
+            dma16(wrsrc, wbase[idx - XLD], xs + XTILE + (4 * (idx - XLD) + wave) * 1024);
+        }
+    };
+    // After the LOADS loads of a step: move this lane's K position on by 128 codes.
+    auto issue_advance = [&]() {
+#pragma unroll
+        for (int i = 0; i < WLD; ++i)
+            if (wbase[i] != OOB) wbase[i] += WROWB;
+        x_k += 128;
+        if (CONV) {
+            x_ci += 128;
+            while (x_ci >= a.Cp) {
+                x_ci -= a.Cp;
+                ++x_tap;
+                if (++x_kw == a.kw) { x_kw = 0; ++x_kh; }
+            }
+        }
+        x_refresh();
+    };
+
+    // ---- accumulators
+    v16f acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int xrow0 = wave * TX + l32;         // this lane's first activation row in the tile
+    const int prow0 = P_IS_W ? l32 : xrow0;
+    const int qrow0 = P_IS_W ? xrow0 : l32;
+    const GenFmt wfm{a.we, a.wm, a.wb}, xfm{a.xe, a.xm, a.xb};
+    const GenFmt pf = P_IS_W ? wfm : xfm, qf = P_IS_W ? xfm : wfm;
+
+    auto compute = [&](int stage, int to_stage) {
+        const uint8_t* xs = smem + stage * STAGE;
+        const uint8_t* ws = xs + XTILE;
+        const uint8_t* ps = P_IS_W ? ws : xs;
+        const uint8_t* qs = P_IS_W ? xs : ws;
+        if constexpr (ACC == FPQ_ACC_FP32) {
+            // 128 codes = 4 rounds of LDS reads x 2 bf16 MFMA steps of 8 codes per lane half.  In round j lane
+            // half g reads codes (2j+g)*16 .. +15 of each of its rows (both operands use the same K order, so
+            // any order is valid).  The loop below is software-pipelined by hand, one slot per MFMA: after MFMA
+            // k of step s come the LDS read of fragment k for the next round and the converts of fragment k
+            // for step s + 1.  A wavefront issues in order and is alone on its SIMD, so the matrix unit only
+            // stays busy if those converts sit between the MFMAs; sched_barrier keeps the slots apart.
+            constexpr int NF = MI + NI, NM = MI * NI;
+            // fragment f is refreshed in slot f % NM (more than one per slot when NM < NF)
+            uint4 raw[2][NF];
+            v8bf frag[2][NF];
+            auto lds_read = [&](int jr, int f) -> uint4 {
+                if (f < MI) {
+                    const int row = prow0 + 32 * f;
+                    if (P4) {
+                        const uint2 v = *reinterpret_cast<const uint2*>(ps + lds_off<PROWB>(row, jr) + g * 8);
+                        return make_uint4(v.x, v.y, 0, 0);
+                    }
+                    return *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 2 * jr + g));
+                }
+                const int row = qrow0 + 32 * (f - MI);
+                if (Q4) {
+                    const uint2 v = *reinterpret_cast<const uint2*>(qs + lds_off<QROWB>(row, jr) + g * 8);
+                    return make_uint4(v.x, v.y, 0, 0);
+                }
+                return *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 2 * jr + g));
+            };
+            auto dec = [&](int st, int f) -> v8bf {
+                const uint4 r = raw[(st >> 1) & 1][f];
+                const int t = st & 1;
+                if (f < MI)
+                    return P4 ? decode8<PKIND>(t ? r.y : r.x, 0u, pf) : decode8<PKIND>(t ? r.z : r.x, t ? r.w : r.y, pf);
+                return Q4 ? decode8<QKIND>(t ? r.y : r.x, 0u, qf) : decode8<QKIND>(t ? r.z : r.x, t ? r.w : r.y, qf);
+            };
+#pragma unroll
+            for (int f = 0; f < NF; ++f) raw[0][f] = lds_read(0, f);
+#pragma unroll
+            for (int f = 0; f < NF; ++f) frag[0][f] = dec(0, f);
+#pragma unroll
+            for (int st = 0; st < 8; ++st) {
+#pragma unroll
+                for (int k = 0; k < NM; ++k) {
+                    const int i = k / NI, jj = k - i * NI;
+                    acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[st & 1][i], frag[st & 1][MI + jj], acc[i][jj],
+                                                                        0, 0, 0);
+#pragma unroll
+                    for (int f = k; f < NF; f += NM) {
+                        if ((st & 1) == 0 && st < 6) raw[((st >> 1) + 1) & 1][f] = lds_read((st >> 1) + 1, f);
+                        if (st < 7) frag[(st + 1) & 1][f] = dec(st + 1, f);
+                    }
+                    // the loads of the step two ahead: one every third slot
+                    if ((st * NM + k) % 3 == 2 && (st * NM + k) / 3 < LOADS) issue_one((st * NM + k) / 3, to_stage);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            static_assert(3 * LOADS <= 8 * NM, "not enough slots for the loads");
+        } else {
+#pragma unroll
+            for (int idx = 0; idx < LOADS; ++idx) issue_one(idx, to_stage);
+            // Two 64-code MFMA steps.  The instruction pairs byte i < 16 of an 8-bit operand (lane half g)
+            // with K index 16g + i and byte 16 + i with 32 + 16g + i, and nibble i of a 4-bit operand with
+            // K index 32g + i; the chunk choices follow from that.
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                v8i pfr[MI], qfr[NI];
+#pragma unroll
+                for (int i = 0; i < MI; ++i) {
+                    const int row = prow0 + 32 * i;
+                    union { v8i v; uint4 q[2]; } u;
+                    if (P4) {
+                        u.q[0] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 2 * kk + g));
+                        u.q[1] = make_uint4(0, 0, 0, 0);
+                    } else {
+                        u.q[0] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 4 * kk + g));
+                        u.q[1] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 4 * kk + 2 + g));
+                    }
+                    pfr[i] = u.v;
+                }
+#pragma unroll
+                for (int i = 0; i < NI; ++i) {
+                    const int row = qrow0 + 32 * i;
+                    union { v8i v; uint4 q[2]; } u;
+                    if (Q4) {
+                        u.q[0] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 2 * kk + g));
+                        u.q[1] = make_uint4(0, 0, 0, 0);
+                    } else {
+                        u.q[0] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 4 * kk + g));
+                        u.q[1] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 4 * kk + 2 + g));
+                    }
+                    qfr[i] = u.v;
+                }
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int jj = 0; jj < NI; ++jj)
+                        acc[i][jj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pfr[i], qfr[jj], acc[i][jj], PFMT, QFMT,
+                                                                                   0, 0, 0, 0);
+            }
+        }
+    };
+
+    // ---- epilogue of one work item: acc * (sx * alpha * sw[n]) + bias[n].
+    // P = activations (accumulator registers run along m), Q = weights (lanes run along n), so the scale
+    // and bias of a lane depend only on the column block j: they are fetched before the K loop of the item.
+    // Row-major [M, N] output: the 32 lanes of a half-wave store 128 consecutive bytes.  NCHW output: the
+    // four registers of a lane are four consecutive pixels, one 16-byte store.
+    const float sxa = (a.sx_dev ? a.sx_dev[0] : a.sx) * a.alpha;
+    float sc[NI], bv[NI];
+    auto epilogue_setup = [&](int n0, int sl) {
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int n = min(n0 + 32 * j + l32, a.N - 1);
+            sc[j] = sxa * a.sw[n];
+            bv[j] = (a.bias && sl == 0) ? a.bias[n] : 0.0f;
+            // keep the values in registers across the K loop (otherwise the loads are re-issued, and
+            // waited for, at every use in the epilogue)
+            asm volatile("" : "+v"(sc[j]), "+v"(bv[j]));
+        }
+    };
+    auto epilogue = [&](int m0, int n0, int sl) {
+        // split-K: slice s writes its scaled partial sums to partial[s]; a second kernel adds the slices
+        float* const yout = a.splits > 1 ? a.partial + (size_t)sl * ((size_t)a.M * a.N) : a.y;
+        const bool full = (m0 + BX <= a.M) && (n0 + BW <= a.N);   // whole tile inside the output
+        const int mw = m0 + wave * TX;                           // first row of this wave
+        if constexpr (!CONV) {
+            const unsigned lane_off = (unsigned)(4 * g * a.N + l32);
+            if (full) {
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        float* rowp = yout + (size_t)(mw + 32 * i + 8 * (r >> 2) + (r & 3)) * a.N + n0;   // uniform
+#pragma unroll
+                        for (int j = 0; j < NI; ++j) rowp[lane_off + 32 * j] = acc[i][j][r] * sc[j] + bv[j];
+                    }
+            } else {
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int m = mw + 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
+#pragma unroll
+                        for (int j = 0; j < NI; ++j) {
+                            const int n = n0 + 32 * j + l32;
+                            if (m < a.M && n < a.N) yout[(size_t)m * a.N + n] = acc[i][j][r] * sc[j] + bv[j];
+                        }
+                    }
+            }
+        } else {
+            const int hw = a.Ho * a.Wo;
+            const bool vec = full && ((hw & 3) == 0) && ((reinterpret_cast<uintptr_t>(yout) & 15) == 0);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const int m = mw + 32 * i + 8 * q4 + 4 * g;
+                    if (vec) {   // hw % 4 == 0: the four pixels lie in one image
+                        const int bi = m / hw;
+                        const int pix = m - bi * hw;
+                        float* mp = yout + (size_t)bi * a.N * hw + pix + (size_t)(n0 + l32) * hw;
+#pragma unroll
+                        for (int j = 0; j < NI; ++j)
+                            *reinterpret_cast<float4*>(mp + (size_t)(32 * j) * hw) =
+                                make_float4(acc[i][j][4 * q4 + 0] * sc[j] + bv[j], acc[i][j][4 * q4 + 1] * sc[j] + bv[j],
+                                            acc[i][j][4 * q4 + 2] * sc[j] + bv[j], acc[i][j][4 * q4 + 3] * sc[j] + bv[j]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            if (m + e >= a.M) continue;
+                            const int bi = (m + e) / hw;
+                            const int pix = (m + e) - bi * hw;
+#pragma unroll
+                            for (int j = 0; j < NI; ++j) {
+                                const int n = n0 + 32 * j + l32;
+                                if (n < a.N) yout[((size_t)bi * a.N + n) * hw + pix] = acc[i][j][4 * q4 + e] * sc[j] + bv[j];
+                            }
+                        }
+                    }
+                }
+        }
+    };
+
+    // ---- main loop over the K steps of all work items of this workgroup.  Each wave issues LOADS buffer
+    // loads per step and they complete in order.  The loads run NSTAGE - 1 steps ahead of the MFMAs,
+    // across item boundaries.  On entry to a step the wave's outstanding loads are the NSTAGE - 1 groups
+    // issued last, so vmcnt <= LOADS * (NSTAGE - 2) means the oldest of them, this step's, has landed; the barrier then says the same of every wave, and that every wave has finished reading the
+    // ring slot of the previous step, which the loads issued during this step overwrite.  The stores of an epilogue also
+    // count in vmcnt and are not ordered against loads, so the first wait after an epilogue drains
+    // everything (vmcnt 0).
+    // Every step issues one group of LOADS loads, NSTAGE - 1 steps ahead of its use; once the work items
+    // run out the group is a dummy (every offset out of range: zeros into a free ring slot, no memory
+    // traffic), which keeps the control flow and the vmcnt arithmetic uniform.
+    int istage = 0;
+    ihas = i_item < nitems;
+    if (ihas) issue_setup();
+    auto issued = [&]() {
+        issue_advance();
+        istage = (istage + 1 == NSTAGE) ? 0 : istage + 1;
+        if (ihas && --i_rem == 0) {
+            i_item += G;
+            ihas = i_item < nitems;
+            if (ihas) {
+                issue_setup();
+            } else {
+                x_sel = 31;
+#pragma unroll
+                for (int i = 0; i < WLD; ++i) wbase[i] = OOB;
+            }
+        }
+    };
+    if (!ihas) {
+        x_sel = 31;
+#pragma unroll
+        for (int i = 0; i < WLD; ++i) wbase[i] = OOB;
+    }
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; ++s) {
+#pragma unroll
+        for (int idx = 0; idx < LOADS; ++idx) issue_one(idx, istage);
+        issued();
+    }
+
+    int cstage = 0;
+    bool drain = false;
+#if defined(FPQ_EXP) && FPQ_EXP == 9
+    long long dbg_t[6] = {0, 0, 0, 0, 0, 0};
+    const long long TK0 = clock64();
+#endif
+    for (int c_item = q; c_item < nitems; c_item += G) {
+        const int tile = c_item / a.splits, sl = c_item - tile * a.splits;
+        const int tx = tile / tiles_w, tw = tile - tx * tiles_w;
+        const int nk = (int)((long)nk_all * (sl + 1) / a.splits) - (int)((long)nk_all * sl / a.splits);
+        epilogue_setup(tw * BW, sl);
+        for (int kt = 0; kt < nk; ++kt) {
+#if defined(FPQ_EXP) && FPQ_EXP == 9
+            const long long T0 = clock64();
+#endif
+            if (NSTAGE == 3 && !drain)
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(LOADS));
+            else
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            drain = false;
+#if defined(FPQ_EXP) && FPQ_EXP == 9
+            const long long T1 = clock64();
+#endif
+            asm volatile("" ::: "memory");
+#if !(defined(FPQ_EXP) && FPQ_EXP == 7)
+            __builtin_amdgcn_s_barrier();
+#endif
+            asm volatile("" ::: "memory");
+#if defined(FPQ_EXP) && FPQ_EXP == 9
+            const long long T2 = clock64();
+#endif
+#if defined(FPQ_EXP) && FPQ_EXP == 9
+            const long long T3 = clock64();
+#endif
+            compute(cstage, istage);   // the loads of the step NSTAGE - 1 ahead ride along with the MFMAs
+            issued();
+#if defined(FPQ_EXP) && FPQ_EXP == 9
+            const long long T4 = clock64();
+            dbg_t[0] += T1 - T0; dbg_t[1] += T2 - T1; dbg_t[2] += T3 - T2; dbg_t[3] += T4 - T3; dbg_t[4] += 1;
+#endif
+            cstage = (cstage + 1 == NSTAGE) ? 0 : cstage + 1;
+        }
+        epilogue(tx * BX, tw * BW, sl);
+        drain = true;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // no load may land in LDS after the workgroup has gone
+#if defined(FPQ_EXP) && FPQ_EXP == 9
+    if (blockIdx.x == 17 && threadIdx.x == 64) {
+        for (int i = 0; i < 5; ++i) a.y[i] = (float)dbg_t[i];
+        a.y[5] = (float)(clock64() - TK0);
+    }
+#endif
+}
+
+// y[i] = sum over slices of partial[s][i]
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, size_t n, int splits,
+                                                            float* __restrict__ y)
+{
+    const size_t nthreads = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (((reinterpret_cast<uintptr_t>(partial) | reinterpret_cast<uintptr_t>(y)) & 15) == 0 && (n & 3) == 0) {
+        const size_t n4 = n >> 2;
+        for (; i < n4; i += nthreads) {
+            float4 acc = reinterpret_cast<const float4*>(partial)[i];
+            for (int s = 1; s < splits; ++s) {
+                const float4 v = reinterpret_cast<const float4*>(partial + (size_t)s * n)[i];
+                acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+            }
+            reinterpret_cast<float4*>(y)[i] = acc;
+        }
+    } else {
+        for (; i < n; i += nthreads) {
+            float acc = partial[i];
+            for (int s = 1; s < splits; ++s) acc += partial[(size_t)s * n + i];
+            y[i] = acc;
+        }
+    }
+}
+
+template <int BX, int BW, int NSTAGE, int XKIND, int WKIND, int ACC, bool CONV>
+static int launch_dma_one(const GemmArgs& a, hipStream_t st)
+{
+    constexpr int WROWB = kind_is_4bit(WKIND) ? 64 : 128;
+    constexpr int smem = NSTAGE * (BX * 128 + (BW * WROWB + 4095) / 4096 * 4096);
+    const int tiles = ((a.M + BX - 1) / BX) * ((a.N + BW - 1) / BW);
+    auto kern = gemm_dma_kernel<BX, BW, NSTAGE, XKIND, WKIND, ACC, CONV>;
+    static bool raised = false;   // per instantiation
+    if (!raised) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
+            hipSuccess)
+            return FPQ_ERR_LAUNCH;
+        raised = true;
+    }
+    const int nitems = tiles * a.splits;
+    constexpr int max_wgs = (BX <= 128) ? 512 : 256;   // resident workgroups: two per compute unit for the small tile
+    hipLaunchKernelGGL(kern, dim3(nitems < max_wgs ? nitems : max_wgs), dim3(256), smem, st, a);
+    if (a.splits > 1) {
+        const size_t n = (size_t)a.M * a.N;
+        size_t grid = (n / 4 + 255) / 256;
+        if (grid < 1) grid = 1;
+        if (grid > 4096) grid = 4096;
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)grid), dim3(256), 0, st, a.partial, n, a.splits, a.y);
+    }
+    return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
+}
+
+template <int XKIND, int WKIND, int ACC>
+static int launch_dma_shape(const GemmArgs& a, hipStream_t st)
+{
+    if (a.tile == TILE_128x160_S2)
+        return a.conv_out ? launch_dma_one<128, 160, 2, XKIND, WKIND, ACC, true>(a, st)
+                          : launch_dma_one<128, 160, 2, XKIND, WKIND, ACC, false>(a, st);
+    return a.conv_out ? launch_dma_one<256, 160, 3, XKIND, WKIND, ACC, true>(a, st)
+                      : launch_dma_one<256, 160, 3, XKIND, WKIND, ACC, false>(a, st);
+}
+
+// Operand kinds the large-tile kernels are instantiated for.
+bool gemm_dma_applicable(const GemmArgs& a)
+{
+    if (a.tile == TILE_GENERIC || a.kh * a.kw > 31) return false;   // tap-validity masks are 31 bits
+    if (a.acc_mode == FPQ_ACC_FP8_MFMA) return a.xkind == OPK_FP8 && (a.wkind == OPK_FP8 || a.wkind == OPK_FP4);
+    return (a.xkind == OPK_FP8 && (a.wkind == OPK_FP8 || a.wkind == OPK_FP4)) ||
+           (a.xkind == OPK_GENERIC8 && (a.wkind == OPK_GENERIC8 || a.wkind == OPK_GENERIC4));
+}
+
+int launch_gemm_dma(const GemmArgs& a, hipStream_t st)
+{
+    if (a.acc_mode == FPQ_ACC_FP8_MFMA) {
+        if (a.xkind == OPK_FP8 && a.wkind == OPK_FP8) return launch_dma_shape<OPK_FP8, OPK_FP8, FPQ_ACC_FP8_MFMA>(a, st);
+        if (a.xkind == OPK_FP8 && a.wkind == OPK_FP4) return launch_dma_shape<OPK_FP8, OPK_FP4, FPQ_ACC_FP8_MFMA>(a, st);
+        return FPQ_ERR_UNSUPPORTED;
+    }
+    if (a.xkind == OPK_FP8 && a.wkind == OPK_FP8) return launch_dma_shape<OPK_FP8, OPK_FP8, FPQ_ACC_FP32>(a, st);
+    if (a.xkind == OPK_FP8 && a.wkind == OPK_FP4) return launch_dma_shape<OPK_FP8, OPK_FP4, FPQ_ACC_FP32>(a, st);
+    if (a.xkind == OPK_GENERIC8 && a.wkind == OPK_GENERIC4) return launch_dma_shape<OPK_GENERIC8, OPK_GENERIC4, FPQ_ACC_FP32>(a, st);
+    if (a.xkind == OPK_GENERIC8 && a.wkind == OPK_GENERIC8) return launch_dma_shape<OPK_GENERIC8, OPK_GENERIC8, FPQ_ACC_FP32>(a, st);
+    return FPQ_ERR_UNSUPPORTED;
+}
+
+}  // namespace fpq

@@ -165,7 +165,8 @@ def run_linear(x, w, h, fx, fw, acc, bias=None, fp32_in=False):
         ws = torch.empty(max(1, B.fpq_gemm_workspace_size(M, N, K, 1)), dtype=torch.uint8, device=DEV)
         B.fpq_gemm(dev(x), 1, fx, sx, None, packed, fw, sw_t, bias_t, y, M, N, K, acc, ws)
     else:
-        B.fpq_gemm(dev(xq), 0, fx, sx, None, packed, fw, sw_t, bias_t, y, M, N, K, acc)
+        ws = torch.empty(max(256, B.fpq_gemm_workspace_size(M, N, K, 0)), dtype=torch.uint8, device=DEV)
+        B.fpq_gemm(dev(xq), 0, fx, sx, None, packed, fw, sw_t, bias_t, y, M, N, K, acc, ws)
     torch.cuda.synchronize()
     return y.cpu().numpy(), (sx, xq, wq, sw)
 
@@ -287,8 +288,10 @@ def run_conv(x, w, h, fx, fw, stride, pad, acc, bias=None, fp32_in=False):
         Cp = B.fpq_padded_channels(Cin)
         codes_nhwc = torch.empty(Bn * H * W * Cp, dtype=torch.uint8, device=DEV)
         B.fpq_quantize_nhwc(dev(x), fx, sx, None, codes_nhwc)
+        ws = torch.empty(max(256, B.fpq_conv2d_workspace_size(Bn, Cin, H, W, Cout, kh, kw, stride, pad, 0)),
+                         dtype=torch.uint8, device=DEV)
         B.fpq_conv2d(codes_nhwc, 0, fx, sx, None, packed, fw, sw_t, bias_t, y, Bn, Cin, H, W, Cout, kh, kw, stride,
-                     pad, acc)
+                     pad, acc, ws)
     torch.cuda.synchronize()
     return y.cpu().numpy(), (sx, xq, wq, sw)
 
@@ -346,3 +349,35 @@ def test_conv_one_hot_taps_exact():
         if 0 <= ho < H and 0 <= wo < W:
             want[0, 17, ho, wo] = 1.0
         assert np.array_equal(y.cpu().numpy(), want)
+
+
+# ------------------------------------------------------------------------------ large-tile (N % 160 == 0) kernels
+
+@pytest.mark.parametrize("M,K,N", [(256, 128, 160), (257, 144, 160), (300, 2880, 320), (1000, 320, 480), (512, 6400, 160),
+                                     (4096, 64, 320)])
+@pytest.mark.parametrize("fxn,fwn,acc", [("E4M3", "E4M3", 0), ("E4M3", "E2M1", 0), ("E3M4", "E3M0", 0), ("E3M4", "E2M5", 0),
+                                         ("E4M3", "E4M3", 1), ("E4M3", "E2M1", 1)])
+def test_linear_large_tile_and_split_k(M, K, N, fxn, fwn, acc):
+    fx, fw = resolved(FORMATS[fxn]), resolved(FORMATS[fwn])
+    x = synth.activations((M, K), 3000 + M)
+    w = synth.weights((N, K), 3500 + N)
+    h = synth.rounding_mask((N, K), 3750 + N)
+    bias = np.linspace(-1, 1, N).astype(np.float32)
+    y, (sx, xq, wq, sw) = run_linear(x, w, h, fx, fw, acc, bias)
+    Y, T = oracle.gemm(xq, fx, sx, wq, fw, sw, bias)
+    check_close(y, Y, T, rel=REL_FP8_MFMA if acc else 1e-5, what="large-tile linear %s" % ((M, K, N, fxn, fwn, acc),))
+
+
+@pytest.mark.parametrize("case", [(1, 32, 16, 16, 160, 3, 1, 1), (2, 48, 13, 11, 320, 3, 1, 1), (4, 160, 9, 9, 160, 3, 2, 1),
+                                  (1, 640, 16, 16, 160, 3, 1, 1), (3, 20, 10, 10, 160, 1, 1, 0), (1, 16, 40, 40, 160, 5, 1, 2)])
+@pytest.mark.parametrize("fxn,fwn,acc", [("E4M3", "E4M3", 0), ("E4M3", "E2M1", 0), ("E3M4", "E3M0", 0), ("E4M3", "E2M1", 1)])
+def test_conv_large_tile_and_split_k(case, fxn, fwn, acc):
+    Bn, Cin, H, W, Cout, k, stride, pad = case
+    fx, fw = resolved(FORMATS[fxn]), resolved(FORMATS[fwn])
+    x = synth.activations((Bn, Cin, H, W), 4000 + Cin)
+    w = synth.weights((Cout, Cin, k, k), 4500 + Cout)
+    h = synth.rounding_mask(w.shape, 4750 + Cout)
+    bias = np.linspace(-0.5, 0.5, Cout).astype(np.float32)
+    y, (sx, xq, wq, sw) = run_conv(x, w, h, fx, fw, stride, pad, acc, bias)
+    Y, T = oracle.conv2d(xq, fx, sx, wq, fw, sw, bias, stride=stride, pad=pad)
+    check_close(y, Y, T, rel=REL_FP8_MFMA if acc else 1e-5, what="large-tile conv %s" % ((case, fxn, fwn, acc),))
