@@ -38,7 +38,6 @@ def parse():
     ap.add_argument("--acc", default="fp32", choices=["fp32", "fp8mfma"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the quantize-bandwidth probe and the other acc mode")
-    ap.add_argument("--per-layer", default=None, help="write a per-layer GEMM timing table to this file")
     return ap.parse_args()
 
 
@@ -117,7 +116,7 @@ def main():
     torch.cuda.synchronize()
     y = torch.empty(max_y, dtype=torch.float32, device=dev)
     ws_buf = torch.empty(max(max_ws, 256), dtype=torch.uint8, device=dev)
-    amax_ws = torch.empty(1024, dtype=torch.float32, device=dev)
+    amax_ws = torch.zeros(1026, dtype=torch.float32, device=dev)   # ticket counter must start at zero
     part_buf = torch.empty(max(max_part, 256), dtype=torch.uint8, device=dev)   # split-K partial sums (codes-input calls)
 
     def run_layer(s, tag, fw, acc_mode):
@@ -138,64 +137,84 @@ def main():
     flops_step = 2 * sum(synth.flops(L) for L in layers)
 
     def timed(acc_mode, steps, warmup):
-        for _ in range(warmup):
+        """Warm up eagerly, capture one step into a HIP graph (the step is ~2000 short launches; issued from
+        Python the host cannot keep the GPU fed), then time `steps` replays."""
+        for _ in range(max(1, warmup)):
             step(acc_mode)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step(acc_mode)
+        graph.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
-            step(acc_mode)
+            graph.replay()
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
     sec = timed(acc, args.steps, args.warmup)
 
-    # ---- per-kernel breakdown: hipEvents around every GEMM launch (quantize done separately so that the
-    # events bracket the GEMM kernel alone), on torch's current stream = the stream the library launches on
-    def gemm_breakdown(acc_mode, reps=3):
-        tot_ms, tot_fl, nlaunch = 0.0, 0.0, 0
-        per_layer = {}
+    # ---- the GEMM kernels alone: every layer's activation codes are prepared first (untimed), then all GEMM /
+    # conv launches of one step (and the split-K reductions that belong to them) are captured into one graph
+    # and timed with hipEvents on the stream they run on
+    codes_bufs = {}
+
+    def prepare_codes():
+        for s in states:
+            L = s.L
+            B.fpq_absmax(s.x, FX[3], s.scale[0:1], s.scale[1:2], amax_ws)
+            if L.kind == "conv":
+                buf = torch.empty(L.B * L.H * L.W * B.fpq_padded_channels(L.Cin), dtype=torch.uint8, device=dev)
+                B.fpq_quantize_nhwc(s.x, FX, 0.0, s.scale[1:2], buf)
+            elif B.fpq_padded_channels(L.K) == L.K:
+                buf = torch.empty(L.M * L.K, dtype=torch.uint8, device=dev)
+                B.fpq_quantize(s.x, FX, 0.0, s.scale[1:2], buf)
+            else:
+                buf = None   # rows need padding: only reachable through the fused entry point
+            codes_bufs[L.name] = buf
+        torch.cuda.synchronize()
+
+    def gemm_only(acc_mode):
+        n = 0
         for tag, fw in (("w8", FW8), ("w4", FW4)):
             for s in states:
                 L = s.L
-                B.fpq_absmax(s.x, FX[3], s.scale[0:1], s.scale[1:2], amax_ws)
+                buf = codes_bufs[L.name]
+                if buf is None:
+                    continue
                 if L.kind == "conv":
-                    B.fpq_quantize_nhwc(s.x, FX, 0.0, s.scale[1:2], ws_buf)
-                elif B.fpq_padded_channels(L.K) == L.K:
-                    B.fpq_quantize(s.x, FX, 0.0, s.scale[1:2], ws_buf)
+                    B.fpq_conv2d(buf, 0, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, y, L.B, L.Cin, L.H,
+                                 L.W, L.Cout, L.k, L.k, L.stride, L.pad, acc_mode, part_buf)
                 else:
-                    continue   # rows need padding: only reachable through the fused entry point
-                best = None
-                for _ in range(reps):
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record()
-                    if L.kind == "conv":
-                        B.fpq_conv2d(ws_buf, 0, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, y, L.B,
-                                     L.Cin, L.H, L.W, L.Cout, L.k, L.k, L.stride, L.pad, acc_mode, part_buf)
-                    else:
-                        B.fpq_gemm(ws_buf, 0, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, y, L.M, L.N,
-                                   L.K, acc_mode, part_buf)
-                    e1.record()
-                    e1.synchronize()
-                    ms = e0.elapsed_time(e1)
-                    best = ms if best is None else best + ms
-                ms = best / reps
-                tot_ms += ms
-                tot_fl += synth.flops(L)
-                nlaunch += 1
-                per_layer[(tag, L.name)] = ms
-        return tot_ms, tot_fl, nlaunch, per_layer
+                    B.fpq_gemm(buf, 0, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, y, L.M, L.N, L.K,
+                               acc_mode, part_buf)
+                n += 1
+        return n
+
+    def gemm_breakdown(acc_mode, reps=5):
+        if not codes_bufs:
+            prepare_codes()
+        nlaunch = gemm_only(acc_mode)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            gemm_only(acc_mode)
+        graph.replay()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            graph.replay()
+        e1.record()
+        e1.synchronize()
+        tot_ms = e0.elapsed_time(e1) / reps
+        tot_fl = 2 * sum(synth.flops(s.L) for s in states if codes_bufs[s.L.name] is not None)
+        return tot_ms, tot_fl, nlaunch, {}
 
     g_ms, g_fl, g_n, per_layer = gemm_breakdown(acc)
-    if args.per_layer:
-        with open(args.per_layer, "w") as fh:
-            fh.write("# weights layer kind M K N k stride GFLOP us TFLOP/s\n")
-            for (tag, name), ms in per_layer.items():
-                L = [l for l in layers if l.name == name][0]
-                fh.write("%s %s %s %d %d %d %d %d %.3f %.2f %.1f\n" % (tag, name, L.kind, L.M, L.K, L.N, L.k, L.stride,
-                         synth.flops(L) / 1e9, ms * 1e3, synth.flops(L) / (ms * 1e-3) / 1e12))
     peak = PEAK_BF16_TFLOPS if acc == B.FPQ_ACC_FP32 else PEAK_FP8_TFLOPS
     achieved = g_fl / (g_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "fpq::gemm_kernel (all launches of one step)", "achieved": round(achieved, 2),
+    roofline = {"bound": "mfma", "kernel": "fpq::gemm_dma_kernel / gemm_kernel (all GEMM and conv launches of one step, one graph)", "achieved": round(achieved, 2),
                 "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
                 "launches": g_n, "avg_launch_us": round(g_ms * 1e3 / g_n, 2),
                 "gemm_ms_per_step": round(g_ms, 4)}
@@ -216,7 +235,7 @@ def main():
         # the other accumulate mode, same step
         other = B.FPQ_ACC_FP8_MFMA if acc == B.FPQ_ACC_FP32 else B.FPQ_ACC_FP32
         sec_o = timed(other, max(2, args.steps // 2), 1)
-        o_ms, o_fl, o_n, _ = gemm_breakdown(other, reps=2)
+        o_ms, o_fl, o_n, _ = gemm_breakdown(other, reps=3)
         peak_o = PEAK_FP8_TFLOPS if other == B.FPQ_ACC_FP8_MFMA else PEAK_BF16_TFLOPS
         out["other_acc_mode"] = {"acc_mode": "fp8mfma" if other == B.FPQ_ACC_FP8_MFMA else "fp32",
                                  "value": round(flops_step / sec_o / 1e12, 3), "unit": "TFLOP/s",

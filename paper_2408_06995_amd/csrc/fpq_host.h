@@ -85,29 +85,29 @@ struct GemmPlan {
     int splits;
 };
 
-// The large-tile kernels need N to be a multiple of 160 (every U-Net width, a multiple of 320, is)
-// and at least one full tile of rows.  Short K (the layer is bound by writing its fp32 output) takes
-// the small tile so that two workgroups per compute unit overlap their store and load phases.  When
-// the tile grid alone would leave compute units idle, K is cut into slices: aim at one workgroup per
-// compute unit, keep at least 4 K steps per slice and at most 256 MB of partial results.
+// The large-tile kernels need N to be a multiple of 160 (every U-Net width, a multiple of 320, is).
+// Deep K with enough 256-row tiles to fill the compute units takes the 256 x 160 tile with three
+// stages (one workgroup per compute unit); everything else takes the 128 x 160 tile with two stages,
+// of which two workgroups fit on a compute unit and overlap each other's load and store phases.
+// When the tile grid alone would leave a quarter of the compute units idle, K is cut into slices: aim
+// at a little more than one workgroup per compute unit, keep at least 4 K steps per slice and at most
+// 256 MB of partial results (each split costs a reduction launch and a round trip of the partials).
 static inline GemmPlan plan_gemm(int64_t M, int64_t N, int64_t Kpad)
 {
     GemmPlan p{TILE_GENERIC, 1};
-    if (N % 160 != 0 || M < 256) return p;
+    if (N % 160 != 0 || M < 1) return p;
     const int64_t nk = Kpad / 128;
-#if defined(FPQ_EXP) && FPQ_EXP == 8
-    p.tile = TILE_256x160_S3;
-    const int64_t tiles = ((M + 255) / 256) * (N / 160);
-    const int64_t want = 256;
-#else
+    const int64_t tiles256 = ((M + 255) / 256) * (N / 160);
+    if (nk >= 16 && tiles256 >= 192) {
+        p.tile = TILE_256x160_S3;
+        return p;
+    }
     p.tile = TILE_128x160_S2;
     const int64_t tiles = ((M + 127) / 128) * (N / 160);
-    const int64_t want = 512;
-#endif
-    if (tiles < want * 3 / 4) {
-        int64_t s = (want + tiles - 1) / tiles;
+    if (tiles < 192 && nk >= 8) {
+        int64_t s = (320 + tiles - 1) / tiles;
         if (s > nk / 4) s = nk / 4;
-        if (s > 16) s = 16;
+        if (s > 32) s = 32;
         while (s > 1 && s * M * N * 4 > ((int64_t)256 << 20)) --s;
         if (s < 1) s = 1;
         p.splits = (int)s;

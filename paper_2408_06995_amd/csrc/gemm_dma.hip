@@ -459,44 +459,22 @@ __global__ __launch_bounds__(256, (BX <= 128 ? 2 : 1)) void gemm_dma_kernel(cons
 
     int cstage = 0;
     bool drain = false;
-#if defined(FPQ_EXP) && FPQ_EXP == 9
-    long long dbg_t[6] = {0, 0, 0, 0, 0, 0};
-    const long long TK0 = clock64();
-#endif
     for (int c_item = q; c_item < nitems; c_item += G) {
         const int tile = c_item / a.splits, sl = c_item - tile * a.splits;
         const int tx = tile / tiles_w, tw = tile - tx * tiles_w;
         const int nk = (int)((long)nk_all * (sl + 1) / a.splits) - (int)((long)nk_all * sl / a.splits);
         epilogue_setup(tw * BW, sl);
         for (int kt = 0; kt < nk; ++kt) {
-#if defined(FPQ_EXP) && FPQ_EXP == 9
-            const long long T0 = clock64();
-#endif
             if (NSTAGE == 3 && !drain)
                 __builtin_amdgcn_s_waitcnt(vmcnt_imm(LOADS));
             else
                 __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
             drain = false;
-#if defined(FPQ_EXP) && FPQ_EXP == 9
-            const long long T1 = clock64();
-#endif
             asm volatile("" ::: "memory");
-#if !(defined(FPQ_EXP) && FPQ_EXP == 7)
             __builtin_amdgcn_s_barrier();
-#endif
             asm volatile("" ::: "memory");
-#if defined(FPQ_EXP) && FPQ_EXP == 9
-            const long long T2 = clock64();
-#endif
-#if defined(FPQ_EXP) && FPQ_EXP == 9
-            const long long T3 = clock64();
-#endif
             compute(cstage, istage);   // the loads of the step NSTAGE - 1 ahead ride along with the MFMAs
             issued();
-#if defined(FPQ_EXP) && FPQ_EXP == 9
-            const long long T4 = clock64();
-            dbg_t[0] += T1 - T0; dbg_t[1] += T2 - T1; dbg_t[2] += T3 - T2; dbg_t[3] += T4 - T3; dbg_t[4] += 1;
-#endif
             cstage = (cstage + 1 == NSTAGE) ? 0 : cstage + 1;
         }
         epilogue(tx * BX, tw * BW, sl);
@@ -509,12 +487,6 @@ __global__ __launch_bounds__(256, (BX <= 128 ? 2 : 1)) void gemm_dma_kernel(cons
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // no load may land in LDS after the workgroup has gone
-#if defined(FPQ_EXP) && FPQ_EXP == 9
-    if (blockIdx.x == 17 && threadIdx.x == 64) {
-        for (int i = 0; i < 5; ++i) a.y[i] = (float)dbg_t[i];
-        a.y[5] = (float)(clock64() - TK0);
-    }
-#endif
 }
 
 // y[i] = sum over slices of partial[s][i]

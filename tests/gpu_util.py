@@ -14,7 +14,7 @@ def dev(a):
 
 
 def gpu_absmax_scale(x_t, maxval):
-    ws = torch.empty(max(1, B.fpq_absmax_workspace_size(x_t.numel()) // 4), dtype=torch.float32, device=DEV)
+    ws = torch.zeros(max(2, B.fpq_absmax_workspace_size(x_t.numel()) // 4), dtype=torch.float32, device=DEV)
     out = torch.empty(2, dtype=torch.float32, device=DEV)
     B.fpq_absmax(x_t, maxval, out[0:1], out[1:2], ws)
     return out

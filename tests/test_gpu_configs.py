@@ -32,7 +32,7 @@ def run_layer_gpu(L, x_t, w_t, h_t, fx, fw, acc, bias_t=None):
     wcodes = torch.empty(L.N * L.K, dtype=torch.uint8, device=DEV)
     B.fpq_pack_weights(w_t.reshape(wshape), fw, None, h_t, packed, sw, wcodes)
     sc = torch.empty(2, dtype=torch.float32, device=DEV)
-    aws = torch.empty(1024, dtype=torch.float32, device=DEV)
+    aws = torch.zeros(1026, dtype=torch.float32, device=DEV)
     B.fpq_absmax(x_t, fx[3], sc[0:1], sc[1:2], aws)
     y = torch.full((L.M * L.N,), float("nan"), dtype=torch.float32, device=DEV)
     if L.kind == "conv":
