@@ -116,7 +116,7 @@ def main():
     torch.cuda.synchronize()
     y = torch.empty(max_y, dtype=torch.float32, device=dev)
     ws_buf = torch.empty(max(max_ws, 256), dtype=torch.uint8, device=dev)
-    amax_ws = torch.zeros(1026, dtype=torch.float32, device=dev)   # ticket counter must start at zero
+    amax_ws = torch.empty(1026, dtype=torch.float32, device=dev)   # partial maxima of the absmax reduction
     part_buf = torch.empty(max(max_part, 256), dtype=torch.uint8, device=dev)   # split-K partial sums (codes-input calls)
 
     def run_layer(s, tag, fw, acc_mode):

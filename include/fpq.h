@@ -132,7 +132,13 @@ int fpq_pack_weights(const float *w, int64_t N, int64_t Cin, int kh, int kw, fpq
  *                   workspace with scale sx / sx_dev.
  * packed_w from fpq_pack_weights(N, K, 1, 1, fw).  sw[N], bias[N] (or NULL) fp32.
  * y[M, N] fp32 row-major.  workspace: fpq_gemm_workspace_size bytes, 256-byte aligned (may be
- * NULL when that size is 0). */
+ * NULL when that size is 0).  It holds the activation codes of the x_is_fp32 == 1 form and, for
+ * shapes with few output tiles and a deep K, the partial sums of the K slices that a second
+ * kernel adds up.  With x_is_fp32 == 0 a missing or smaller workspace is not an error: the layer
+ * then runs unsliced (same result up to summation order, slower for those shapes).  With
+ * x_is_fp32 == 1 a workspace below the stated size returns FPQ_ERR_WORKSPACE.  The contents need
+ * no initialisation and mean nothing after the call; calls that share a workspace must be
+ * ordered on one stream. */
 size_t fpq_gemm_workspace_size(int64_t M, int64_t N, int64_t K, int x_is_fp32);
 int fpq_gemm(const void *x, int x_is_fp32, fpq_format_t fx, float sx, const float *sx_dev,
              const void *packed_w, fpq_format_t fw, const float *sw, const float *bias, float *y,
