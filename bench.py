@@ -2,9 +2,10 @@
 """Benchmark of the quantized-layer hot path on one MI355X.
 
 One step = one pass of the whole path over one batch of synthetic input: for every layer of the
-workload, absmax calibration of the fp32 activation (device-resident scale), activation quantize
-to E4M3 codes, and the quantized linear / conv layer on pre-packed weights -- once with E4M3
-weights (W8A8) and once with E2M1 weights (W4A8).  Weight packing is the offline step and is done
+workload, absmax calibration of the fp32 activation (the per-tensor scale never leaves the device),
+activation quantize to E4M3 codes, and the quantized linear / conv layer on pre-packed weights --
+all three inside one fpq_gemm / fpq_conv2d call in its dynamic-scale mode -- once with E4M3 weights
+(W8A8) and once with E2M1 weights (W4A8).  Weight packing is the offline step and is done
 before the timed region; inputs are resident in HBM.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg4|cfg3|cfg2|cfg1]
@@ -89,11 +90,11 @@ def main():
         if L.kind == "conv":
             s.x = synth.activations_torch((L.B, L.Cin, L.H, L.W), sx_seed, dev)
             wshape = (L.Cout, L.Cin, L.k, L.k)
-            ws = B.fpq_conv2d_workspace_size(L.B, L.Cin, L.H, L.W, L.Cout, L.k, L.k, L.stride, L.pad, 1)
+            ws = B.fpq_conv2d_workspace_size(L.B, L.Cin, L.H, L.W, L.Cout, L.k, L.k, L.stride, L.pad, 2)
         else:
             s.x = synth.activations_torch((L.M, L.K), sx_seed, dev)
             wshape = (L.N, L.K)
-            ws = B.fpq_gemm_workspace_size(L.M, L.N, L.K, 1)
+            ws = B.fpq_gemm_workspace_size(L.M, L.N, L.K, 2)
         w = synth.weights_torch(wshape, sw_seed, dev)
         h = synth.rounding_mask_torch(wshape, sh_seed, dev)
         kk = L.k if L.kind == "conv" else 1
@@ -121,13 +122,12 @@ def main():
 
     def run_layer(s, tag, fw, acc_mode):
         L = s.L
-        B.fpq_absmax(s.x, FX[3], s.scale[0:1], s.scale[1:2], amax_ws)
         if L.kind == "conv":
-            B.fpq_conv2d(s.x, 1, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, y, L.B, L.Cin, L.H, L.W,
-                         L.Cout, L.k, L.k, L.stride, L.pad, acc_mode, ws_buf)
+            B.fpq_conv2d(s.x, B.FPQ_X_FP32_DYNAMIC, FX, 0.0, None, s.packed[tag], fw, s.sw[tag], None, y, L.B, L.Cin,
+                         L.H, L.W, L.Cout, L.k, L.k, L.stride, L.pad, acc_mode, ws_buf)
         else:
-            B.fpq_gemm(s.x, 1, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, y, L.M, L.N, L.K, acc_mode,
-                       ws_buf)
+            B.fpq_gemm(s.x, B.FPQ_X_FP32_DYNAMIC, FX, 0.0, None, s.packed[tag], fw, s.sw[tag], None, y, L.M, L.N, L.K,
+                       acc_mode, ws_buf)
 
     def step(acc_mode):
         for tag, fw in (("w8", FW8), ("w4", FW4)):

@@ -65,6 +65,14 @@ typedef enum fpq_status {
  *   below it, so the error bound is 7 * 2^-13 * sum|a_k b_k| instead. */
 typedef enum fpq_acc_mode { FPQ_ACC_FP32 = 0, FPQ_ACC_FP8_MFMA = 1 } fpq_acc_mode;
 
+/* What the x argument of fpq_gemm / fpq_conv2d holds (their x_is_fp32 argument).
+ * FPQ_X_CODES: codes written by fpq_quantize / fpq_quantize_nhwc with scale sx.
+ * FPQ_X_FP32: fp32 activations; the library quantizes them first with the given scale sx / sx_dev.
+ * FPQ_X_FP32_DYNAMIC: fp32 activations and no scale: the library finds the per-tensor scale
+ *   absmax(x) / maxval itself (what fpq_absmax computes, bit for bit) on the way; sx and sx_dev are
+ *   ignored.  One launch fewer than fpq_absmax followed by FPQ_X_FP32. */
+typedef enum fpq_x_kind { FPQ_X_CODES = 0, FPQ_X_FP32 = 1, FPQ_X_FP32_DYNAMIC = 2 } fpq_x_kind;
+
 const char *fpq_strerror(int status);
 
 /* ---- host helpers (no GPU needed) ------------------------------------------------------- */
@@ -116,10 +124,12 @@ int fpq_dequantize(const uint8_t *codes, size_t n, fpq_format_t f, float scale, 
  * scale[n] (given, or fl32(absmax_n / maxval), 1 for an all-zero row), then each element is
  * quantized with Eq. (12) and its mask entry h (0 = floor, non-zero = floor + 1 step), or with
  * Eq. (8) when mask == NULL (the paper applies no rounding learning to FP8 weights).
- * packed receives fpq_packed_size(...) bytes: a 64-byte header, then the codes in the layout the
- * GEMM kernels stream (K ordered (kh, kw, ci), ci padded to 16, K padded to 128; 4-bit formats two
- * per byte).  scale_out[N] receives the scales used.  codes_out, if not NULL, receives the plain
- * codes [N, Cin, kh, kw], one per byte, for inspection. */
+ * packed receives fpq_packed_size(...) bytes: a header (256 bytes, 64 used), then the codes in the
+ * layout the GEMM kernels stream (K ordered (kh, kw, ci), ci padded to 16, K padded to 128; 4-bit
+ * formats two per byte).  packed must be 16-byte aligned; 256-byte alignment is what the kernels
+ * are tuned for (every 128-byte piece of a row is then one cache line).  scale_out[N] receives
+ * the scales used.  codes_out, if not NULL, receives the plain codes [N, Cin, kh, kw], one per
+ * byte, for inspection. */
 size_t fpq_packed_size(int64_t N, int64_t Cin, int kh, int kw, fpq_format_t f);
 int fpq_pack_weights(const float *w, int64_t N, int64_t Cin, int kh, int kw, fpq_format_t f,
                      const float *scale, const uint8_t *mask, void *packed, size_t packed_bytes,
@@ -129,7 +139,8 @@ int fpq_pack_weights(const float *w, int64_t N, int64_t Cin, int kh, int kw, fpq
 
 /* Linear layer.  x: x_is_fp32 == 0: codes [M, K], one per byte, K % 16 == 0, 16-byte aligned;
  *                   x_is_fp32 == 1: fp32 [M, K], quantized by the library first (any K) into the
- *                   workspace with scale sx / sx_dev.
+ *                   workspace with scale sx / sx_dev;
+ *                   x_is_fp32 == 2: the same with the scale absmax(x) / maxval found by the library.
  * packed_w from fpq_pack_weights(N, K, 1, 1, fw).  sw[N], bias[N] (or NULL) fp32.
  * y[M, N] fp32 row-major.  workspace: fpq_gemm_workspace_size bytes, 256-byte aligned (may be
  * NULL when that size is 0).  It holds the activation codes of the x_is_fp32 == 1 form and, for
@@ -147,7 +158,8 @@ int fpq_gemm(const void *x, int x_is_fp32, fpq_format_t fx, float sx, const floa
 
 /* 2-D convolution, zero padding, square stride, as an implicit GEMM with M = B*Ho*Wo,
  * K = Cin*kh*kw, N = Cout.  x: x_is_fp32 == 0: codes [B, H, W, Cp] from fpq_quantize_nhwc;
- * x_is_fp32 == 1: fp32 NCHW [B, Cin, H, W], quantized by the library first into the workspace.
+ * x_is_fp32 == 1 or 2 (fpq_x_kind): fp32 NCHW [B, Cin, H, W], quantized by the library first into
+ * the workspace.
  * y: fp32 NCHW [B, Cout, Ho, Wo], Ho = (H + 2 pad - kh) / stride + 1. */
 size_t fpq_conv2d_workspace_size(int64_t B, int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh,
                                  int kw, int stride, int pad, int x_is_fp32);

@@ -13,6 +13,9 @@ LIB_PATH = os.path.join(HERE, "libfpq.so")
 
 FPQ_ACC_FP32 = 0
 FPQ_ACC_FP8_MFMA = 1
+FPQ_X_CODES = 0
+FPQ_X_FP32 = 1
+FPQ_X_FP32_DYNAMIC = 2
 
 
 class fpq_format_t(C.Structure):

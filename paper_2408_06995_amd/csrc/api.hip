@@ -108,6 +108,9 @@ __global__ void write_header_kernel(PackedHeader h, uint32_t* dst)
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Tail of the workspace in dynamic-scale mode: 1024 partial maxima, then [scale, absmax].
+constexpr size_t kDynScaleBytes = 1024 * sizeof(float) + 256;
+
 }  // namespace
 
 extern "C" {
@@ -177,7 +180,8 @@ int fpq_quantize(const float* x, size_t n, fpq_format_t f, float scale, const fl
     if (n == 0) return FPQ_OK;
     if (!x || !codes) return FPQ_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(x) & 3) return FPQ_ERR_ALIGN;
-    return launch_quantize(x, n, q, is_four_bit(f), scale, scale_dev, codes, static_cast<hipStream_t>(stream));
+    const ScaleSrc ss{scale, scale_dev, nullptr, 0, 0.0f, nullptr};
+    return launch_quantize(x, n, q, is_four_bit(f), ss, codes, static_cast<hipStream_t>(stream));
 }
 
 int64_t fpq_padded_channels(int64_t C) { return C > 0 ? padded_channels(C) : 0; }
@@ -193,7 +197,8 @@ int fpq_quantize_nhwc(const float* x, int64_t B, int64_t C, int64_t H, int64_t W
     if (B > 65535 || H * W > (1 << 24) || B * H * W * padded_channels(C) >= (int64_t)1 << 31) return FPQ_ERR_SHAPE;
     if (!x || !codes) return FPQ_ERR_NULL;
     if ((reinterpret_cast<uintptr_t>(x) & 3) || (reinterpret_cast<uintptr_t>(codes) & 15)) return FPQ_ERR_ALIGN;
-    return launch_quantize_nhwc(x, B, C, H, W, q, scale, scale_dev, codes, static_cast<hipStream_t>(stream));
+    const ScaleSrc ss{scale, scale_dev, nullptr, 0, 0.0f, nullptr};
+    return launch_quantize_nhwc(x, B, C, H, W, q, ss, codes, static_cast<hipStream_t>(stream));
 }
 
 int fpq_dequantize(const uint8_t* codes, size_t n, fpq_format_t f, float scale, float* out, void* stream)
@@ -211,7 +216,7 @@ size_t fpq_packed_size(int64_t N, int64_t Cin, int kh, int kw, fpq_format_t f)
     if (N <= 0 || Cin <= 0 || kh <= 0 || kw <= 0 || resolve_format(f, nullptr)) return 0;
     size_t kpad = (size_t)padded_k(Cin, (int64_t)kh * kw);
     size_t row = is_four_bit(f) ? kpad / 2 : kpad;
-    return sizeof(PackedHeader) + (size_t)N * row;
+    return kPackedRowsOffset + (size_t)N * row;
 }
 
 int fpq_pack_weights(const float* w, int64_t N, int64_t Cin, int kh, int kw, fpq_format_t f, const float* scale,
@@ -243,14 +248,15 @@ int fpq_pack_weights(const float* w, int64_t N, int64_t Cin, int kh, int kw, fpq
     h.Kpad = (int32_t)padded_k(Cin, (int64_t)kh * kw);
     hipLaunchKernelGGL(write_header_kernel, dim3(1), dim3(64), 0, s, h, static_cast<uint32_t*>(packed));
     return launch_pack_weights(w, N, Cin, kh * kw, q, is_four_bit(f), scale, mask,
-                               static_cast<uint8_t*>(packed) + sizeof(PackedHeader), scale_out, codes_out, s);
+                               static_cast<uint8_t*>(packed) + kPackedRowsOffset, scale_out, codes_out, s);
 }
 
 size_t fpq_gemm_workspace_size(int64_t M, int64_t N, int64_t K, int x_is_fp32)
 {
     if (M <= 0 || K <= 0 || N <= 0) return 0;
     size_t codes = x_is_fp32 ? align_up((size_t)M * (size_t)padded_channels(K), 256) : 0;
-    return codes + split_workspace_bytes(plan_gemm(M, N, padded_k(K, 1)), M, N);
+    return codes + align_up(split_workspace_bytes(plan_gemm(M, N, padded_k(K, 1)), M, N), 256) +
+           (x_is_fp32 == FPQ_X_FP32_DYNAMIC ? kDynScaleBytes : 0);
 }
 
 size_t fpq_conv2d_workspace_size(int64_t B, int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh, int kw,
@@ -260,7 +266,10 @@ size_t fpq_conv2d_workspace_size(int64_t B, int64_t Cin, int64_t H, int64_t W, i
     if (H + 2 * pad < kh || W + 2 * pad < kw) return 0;
     const int64_t Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
     size_t codes = x_is_fp32 ? align_up((size_t)B * H * W * (size_t)padded_channels(Cin), 256) : 0;
-    return codes + split_workspace_bytes(plan_gemm(B * Ho * Wo, Cout, padded_k(Cin, (int64_t)kh * kw)), B * Ho * Wo, Cout);
+    return codes +
+           align_up(split_workspace_bytes(plan_gemm(B * Ho * Wo, Cout, padded_k(Cin, (int64_t)kh * kw)), B * Ho * Wo, Cout),
+                    256) +
+           (x_is_fp32 == FPQ_X_FP32_DYNAMIC ? kDynScaleBytes : 0);
 }
 
 static int run_layer(const void* x, int x_is_fp32, fpq_format_t fx, float sx, const float* sx_dev,
@@ -273,7 +282,9 @@ static int run_layer(const void* x, int x_is_fp32, fpq_format_t fx, float sx, co
     if (st) return st;
     st = resolve_format(fw, &qw);
     if (st) return st;
-    if (!sx_dev && !scale_ok(sx)) return FPQ_ERR_SCALE;
+    if (x_is_fp32 < 0 || x_is_fp32 > FPQ_X_FP32_DYNAMIC) return FPQ_ERR_UNSUPPORTED;
+    const bool dyn = x_is_fp32 == FPQ_X_FP32_DYNAMIC;
+    if (!dyn && !sx_dev && !scale_ok(sx)) return FPQ_ERR_SCALE;
     if (B <= 0 || Cin <= 0 || H <= 0 || W <= 0 || Cout <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0)
         return FPQ_ERR_SHAPE;
     if (H + 2 * pad < kh || W + 2 * pad < kw || H > 16000 || W > 16000 || kh > 64 || kw > 64 || pad > 64)
@@ -296,21 +307,36 @@ static int run_layer(const void* x, int x_is_fp32, fpq_format_t fx, float sx, co
     // codes and no (or too small a) workspace gets the unsplit kernel
     GemmPlan plan = plan_gemm(M, Cout, padded_k(Cin, (int64_t)kh * kw));
     const size_t codes_bytes = x_is_fp32 ? align_up((size_t)B * H * W * (size_t)Cp, 256) : 0;
-    const size_t part_bytes = split_workspace_bytes(plan, M, Cout);
+    const size_t part_bytes = align_up(split_workspace_bytes(plan, M, Cout), 256);
     if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255)) return FPQ_ERR_ALIGN;
-    if (x_is_fp32 && (!workspace || workspace_bytes < codes_bytes + part_bytes)) return FPQ_ERR_WORKSPACE;
+    if (x_is_fp32 && (!workspace || workspace_bytes < codes_bytes + part_bytes + (dyn ? kDynScaleBytes : 0)))
+        return FPQ_ERR_WORKSPACE;
     if (!x_is_fp32 && (!workspace || workspace_bytes < part_bytes)) plan.splits = 1;
     float* partial = plan.splits > 1 ? reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + codes_bytes) : nullptr;
     if (x_is_fp32) {
         if (reinterpret_cast<uintptr_t>(x) & 3) return FPQ_ERR_ALIGN;
         uint8_t* buf = static_cast<uint8_t*>(workspace);
+        ScaleSrc ss{sx, sx_dev, nullptr, 0, 0.0f, nullptr};
+        if (dyn) {
+            // per-tensor scale = absmax(x) / maxval found here: one reduction launch leaves per-block maxima,
+            // the quantize kernel folds them and publishes the scale the layer kernel reads
+            float* dynbuf = reinterpret_cast<float*>(buf + codes_bytes + part_bytes);
+            const size_t nx = (size_t)B * Cin * H * W;
+            st = launch_absmax_partials(static_cast<const float*>(x), nx, dynbuf, s);
+            if (st) return st;
+            ss.partials = dynbuf;
+            ss.nparts = absmax_parts(nx);
+            ss.maxval = qx.c;
+            ss.publish = dynbuf + 1024;
+            sx_dev = dynbuf + 1024;
+        }
         if (conv_out) {
-            st = launch_quantize_nhwc(static_cast<const float*>(x), B, Cin, H, W, qx, sx, sx_dev, buf, s);
+            st = launch_quantize_nhwc(static_cast<const float*>(x), B, Cin, H, W, qx, ss, buf, s);
         } else if (Cp == Cin) {
-            st = launch_quantize(static_cast<const float*>(x), (size_t)M * Cin, qx, false, sx, sx_dev, buf, s);
+            st = launch_quantize(static_cast<const float*>(x), (size_t)M * Cin, qx, false, ss, buf, s);
         } else {
             // rows padded to Cp codes: a linear layer is a 1x1 "image" per row with Cin channels
-            st = launch_quantize_nhwc(static_cast<const float*>(x), M, Cin, 1, 1, qx, sx, sx_dev, buf, s);
+            st = launch_quantize_nhwc(static_cast<const float*>(x), M, Cin, 1, 1, qx, ss, buf, s);
         }
         if (st) return st;
         xcodes = buf;
@@ -322,7 +348,7 @@ static int run_layer(const void* x, int x_is_fp32, fpq_format_t fx, float sx, co
     GemmArgs a;
     memset(&a, 0, sizeof a);
     a.x = xcodes;
-    a.wrows = static_cast<const uint8_t*>(packed_w) + sizeof(PackedHeader);
+    a.wrows = static_cast<const uint8_t*>(packed_w) + kPackedRowsOffset;
     a.sw = sw;
     a.bias = bias;
     a.sx_dev = sx_dev;

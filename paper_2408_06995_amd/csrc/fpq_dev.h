@@ -71,6 +71,19 @@ __device__ __forceinline__ float inv_scale(float scale, const float* scale_dev)
     return __fdiv_rn(1.0f, s);
 }
 
+// Where a quantize kernel takes its per-tensor scale from: a host value, a device value, or (dynamic
+// scale) the per-block partial maxima of |x| that absmax_partial_kernel left behind, in which case every
+// block folds them again and derives scale = absmax / maxval itself (no launch of its own for that),
+// and the first block publishes [scale, absmax] for the layer kernel that follows.
+struct ScaleSrc {
+    float host;
+    const float* dev;
+    const float* partials;
+    int nparts;
+    float maxval;
+    float* publish;
+};
+
 // Eq. (5) decode of one code to fp32 (p = 0 row: zero and subnormals).  Exact.
 __device__ __forceinline__ float decode_code(uint32_t code, int e, int m, int b)
 {

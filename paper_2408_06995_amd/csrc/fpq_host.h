@@ -10,6 +10,7 @@
 namespace fpq {
 
 struct QParams;
+struct ScaleSrc;
 
 // Channels of a channels-last code buffer: C rounded up to a whole 16-byte chunk.
 static inline int64_t padded_channels(int64_t C) { return (C + 15) / 16 * 16; }
@@ -24,7 +25,9 @@ static inline int absmax_parts(size_t n)
     return (int)(g > 1024 ? 1024 : g);
 }
 
-// 64-byte header in front of the packed rows.
+// Header in front of the packed rows.  The rows start kPackedRowsOffset bytes into the buffer so that, for a
+// 256-byte aligned buffer, every 128-byte K chunk of a row is one whole cache line (a chunk that straddles two
+// lines halves the rate of the LDS loads).
 struct PackedHeader {
     uint32_t magic;      // 'FPQW'
     uint32_t layout;     // 1
@@ -36,6 +39,7 @@ struct PackedHeader {
     uint32_t reserved[2];
 };
 static_assert(sizeof(PackedHeader) == 64, "header is 64 bytes");
+constexpr size_t kPackedRowsOffset = 256;
 constexpr uint32_t kPackedMagic = 0x57515046u;
 
 // How an operand's codes reach the matrix unit.
@@ -121,10 +125,11 @@ static inline size_t split_workspace_bytes(const GemmPlan& p, int64_t M, int64_t
 
 int launch_absmax(const float* x, size_t n, float maxval, float* absmax_out, float* scale_out, float* partial,
                   hipStream_t st);
-int launch_quantize(const float* x, size_t n, const QParams& q, bool four_bit, float scale, const float* scale_dev,
-                    uint8_t* codes, hipStream_t st);
-int launch_quantize_nhwc(const float* x, int64_t B, int64_t C, int64_t H, int64_t W, const QParams& q, float scale,
-                         const float* scale_dev, uint8_t* codes, hipStream_t st);
+int launch_absmax_partials(const float* x, size_t n, float* partial, hipStream_t st);
+int launch_quantize(const float* x, size_t n, const QParams& q, bool four_bit, const ScaleSrc& ss, uint8_t* codes,
+                    hipStream_t st);
+int launch_quantize_nhwc(const float* x, int64_t B, int64_t C, int64_t H, int64_t W, const QParams& q,
+                         const ScaleSrc& ss, uint8_t* codes, hipStream_t st);
 int launch_dequantize(const uint8_t* codes, size_t n, int e, int m, int b, float scale, float* out, hipStream_t st);
 int launch_pack_weights(const float* w, int64_t N, int64_t Cin, int taps, const QParams& q, bool four_bit,
                         const float* scale_in, const uint8_t* mask, uint8_t* packed_rows, float* scale_out,

@@ -51,6 +51,35 @@ __device__ __forceinline__ v4i make_rsrc(const void* base, unsigned bytes)
 // expcnt 6:4 and lgkmcnt 11:8 left at their maxima).
 constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
 
+// Exchange helpers for the epilogue's 4 x 4 transpose: the value of the lane whose number differs in bit 0
+// (or bit 1) within the same quad of lanes.
+__device__ __forceinline__ float quad_xor1(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float quad_xor2(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));
+}
+// v[i] of quad lane b becomes what v[b] of quad lane i was (b0, b1 = bits of the lane's position in its quad).
+__device__ __forceinline__ void quad_transpose(float (&v)[4], bool b0, bool b1)
+{
+#pragma unroll
+    for (int p = 0; p < 4; p += 2) {
+        const float lo = v[p], hi = v[p + 1];
+        const float xhi = quad_xor1(hi), xlo = quad_xor1(lo);
+        v[p] = b0 ? xhi : lo;
+        v[p + 1] = b0 ? hi : xlo;
+    }
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const float lo = v[p], hi = v[p + 2];
+        const float xhi = quad_xor2(hi), xlo = quad_xor2(lo);
+        v[p] = b1 ? xhi : lo;
+        v[p + 2] = b1 ? hi : xlo;
+    }
+}
+
 template <int BX, int BW, int NSTAGE, int XKIND, int WKIND, int ACC, bool CONV>
 __global__ __launch_bounds__(256, (BX <= 128 ? 2 : 1)) void gemm_dma_kernel(const GemmArgs a)
 {
@@ -230,138 +259,206 @@ __global__ __launch_bounds__(256, (BX <= 128 ? 2 : 1)) void gemm_dma_kernel(cons
     const GenFmt wfm{a.we, a.wm, a.wb}, xfm{a.xe, a.xm, a.xb};
     const GenFmt pf = P_IS_W ? wfm : xfm, qf = P_IS_W ? xfm : wfm;
 
-    auto compute = [&](int stage, int to_stage) {
+    // ---- FPQ_ACC_FP32: one K step = 128 codes = 4 rounds of LDS reads x 2 bf16 MFMA steps of 8 codes per
+    // lane half.  In round j lane half g reads codes (2j+g)*16 .. +15 of each of its rows (both operands use
+    // the same K order, so any order is valid).  The loop is software-pipelined by hand, one slot per MFMA:
+    // after MFMA k of step st come the LDS read of fragment k for the next round and the converts of
+    // fragment k for step st + 1.  A wavefront issues in order and is alone on its SIMD (or one of two), so
+    // the matrix unit only stays busy if those reads and converts sit between the MFMAs; sched_barrier
+    // keeps the slots apart.  The pipeline runs across K steps and work items: the last two MFMA steps of
+    // a K step read and convert the first fragments of the next ring slot, after the wait + barrier that
+    // make that slot valid (tail_sync), so raw[0] / frag[0] are live on entry to every K step.
+    constexpr int NF = MI + NI, NM = MI * NI;
+    uint4 raw[2][NF];
+    v8bf frag[2][NF];
+    auto lds_read = [&](int stage, int jr, int f) -> uint4 {
         const uint8_t* xs = smem + stage * STAGE;
         const uint8_t* ws = xs + XTILE;
         const uint8_t* ps = P_IS_W ? ws : xs;
         const uint8_t* qs = P_IS_W ? xs : ws;
-        if constexpr (ACC == FPQ_ACC_FP32) {
-            // 128 codes = 4 rounds of LDS reads x 2 bf16 MFMA steps of 8 codes per lane half.  In round j lane
-            // half g reads codes (2j+g)*16 .. +15 of each of its rows (both operands use the same K order, so
-            // any order is valid).  The loop below is software-pipelined by hand, one slot per MFMA: after MFMA
-            // k of step s come the LDS read of fragment k for the next round and the converts of fragment k
-            // for step s + 1.  A wavefront issues in order and is alone on its SIMD, so the matrix unit only
-            // stays busy if those converts sit between the MFMAs; sched_barrier keeps the slots apart.
-            constexpr int NF = MI + NI, NM = MI * NI;
-            // fragment f is refreshed in slot f % NM (more than one per slot when NM < NF)
-            uint4 raw[2][NF];
-            v8bf frag[2][NF];
-            auto lds_read = [&](int jr, int f) -> uint4 {
-                if (f < MI) {
-                    const int row = prow0 + 32 * f;
-                    if (P4) {
-                        const uint2 v = *reinterpret_cast<const uint2*>(ps + lds_off<PROWB>(row, jr) + g * 8);
-                        return make_uint4(v.x, v.y, 0, 0);
+        if (f < MI) {
+            const int row = prow0 + 32 * f;
+            if (P4) {
+                const uint2 v = *reinterpret_cast<const uint2*>(ps + lds_off<PROWB>(row, jr) + g * 8);
+                return make_uint4(v.x, v.y, 0, 0);
+            }
+            return *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 2 * jr + g));
+        }
+        const int row = qrow0 + 32 * (f - MI);
+        if (Q4) {
+            const uint2 v = *reinterpret_cast<const uint2*>(qs + lds_off<QROWB>(row, jr) + g * 8);
+            return make_uint4(v.x, v.y, 0, 0);
+        }
+        return *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 2 * jr + g));
+    };
+    auto dec = [&](int st, int f) -> v8bf {
+        const uint4 r = raw[(st >> 1) & 1][f];
+        const int t = st & 1;
+        if (f < MI)
+            return P4 ? decode8<PKIND>(t ? r.y : r.x, 0u, pf) : decode8<PKIND>(t ? r.z : r.x, t ? r.w : r.y, pf);
+        return Q4 ? decode8<QKIND>(t ? r.y : r.x, 0u, qf) : decode8<QKIND>(t ? r.z : r.x, t ? r.w : r.y, qf);
+    };
+    auto first_fragments = [&](int stage) {
+#pragma unroll
+        for (int f = 0; f < NF; ++f) raw[0][f] = lds_read(stage, 0, f);
+#pragma unroll
+        for (int f = 0; f < NF; ++f) frag[0][f] = dec(0, f);
+    };
+
+    // Wait until the loads of the next K step have landed, then meet the other waves: after the barrier
+    // every wave's share of that ring slot is valid, and every wave has finished reading the ring slot
+    // of the current step (its last LDS read was consumed an MFMA step ago), which the loads issued
+    // from the next step on overwrite.  Buffer loads and stores of a wave retire in issue order, so
+    // "vmcnt <= n" means that all but the n youngest operations are complete.  Youngest operations at
+    // this point, for three stages: the LOADS loads issued during this step; in the first step of a
+    // work item before them the two scale / bias loads and the stores of the previous item's epilogue
+    // (the counter saturates at 63, hence the min).  With two stages the wanted loads are themselves
+    // the youngest, so the wait is for zero.
+    enum { W_NORMAL = 0, W_FIRST = 1, W_AFTER_STORES = 2, W_DRAIN = 3 };
+    constexpr int SFULL = CONV ? MI * 4 * NI : MI * 16 * NI;   // store instructions of the epilogue of a whole tile
+    auto tail_sync = [&](int mode) {
+        if (NSTAGE == 2 || mode == W_DRAIN)
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        else if (mode == W_NORMAL)
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(LOADS));
+        else if (mode == W_FIRST)
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(LOADS + 2));
+        else
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(LOADS + 2 + SFULL < 63 ? LOADS + 2 + SFULL : 63));
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+
+    auto compute = [&](int stage, int next_stage, int to_stage, int mode) {
+#pragma unroll
+        for (int st = 0; st < 8; ++st) {
+#pragma unroll
+            for (int k = 0; k < NM; ++k) {
+                const int i = k / NI, jj = k - i * NI;
+                acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[st & 1][i], frag[st & 1][MI + jj], acc[i][jj],
+                                                                    0, 0, 0);
+                if (st == 6 && k == 0) tail_sync(mode);
+#pragma unroll
+                for (int f = k; f < NF; f += NM) {
+                    if ((st & 1) == 0) {
+                        if (st < 6)
+                            raw[((st >> 1) + 1) & 1][f] = lds_read(stage, (st >> 1) + 1, f);
+                        else
+                            raw[0][f] = lds_read(next_stage, 0, f);
                     }
-                    return *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 2 * jr + g));
+                    frag[(st + 1) & 1][f] = dec((st + 1) & 7, f);
                 }
-                const int row = qrow0 + 32 * (f - MI);
+                // the loads of the step NSTAGE - 1 ahead: one every third slot
+                if ((st * NM + k) % 3 == 2 && (st * NM + k) / 3 < LOADS) issue_one((st * NM + k) / 3, to_stage);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        static_assert(3 * LOADS <= 6 * NM, "the loads of a step must be issued before its tail_sync");
+    };
+
+    // ---- FPQ_ACC_FP8_MFMA: codes feed the 8-bit / 4-bit MFMA directly, two 64-code steps per K step.  The
+    // instruction pairs byte i < 16 of an 8-bit operand (lane half g) with K index 16g + i and byte 16 + i
+    // with 32 + 16g + i, and nibble i of a 4-bit operand with K index 32g + i; the chunk choices follow.
+    auto compute8 = [&](int stage, int to_stage) {
+        const uint8_t* xs = smem + stage * STAGE;
+        const uint8_t* ws = xs + XTILE;
+        const uint8_t* ps = P_IS_W ? ws : xs;
+        const uint8_t* qs = P_IS_W ? xs : ws;
+#pragma unroll
+        for (int idx = 0; idx < LOADS; ++idx) issue_one(idx, to_stage);
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            v8i pfr[MI], qfr[NI];
+#pragma unroll
+            for (int i = 0; i < MI; ++i) {
+                const int row = prow0 + 32 * i;
+                union { v8i v; uint4 q[2]; } u;
+                if (P4) {
+                    u.q[0] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 2 * kk + g));
+                    u.q[1] = make_uint4(0, 0, 0, 0);
+                } else {
+                    u.q[0] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 4 * kk + g));
+                    u.q[1] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 4 * kk + 2 + g));
+                }
+                pfr[i] = u.v;
+            }
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                const int row = qrow0 + 32 * i;
+                union { v8i v; uint4 q[2]; } u;
                 if (Q4) {
-                    const uint2 v = *reinterpret_cast<const uint2*>(qs + lds_off<QROWB>(row, jr) + g * 8);
-                    return make_uint4(v.x, v.y, 0, 0);
+                    u.q[0] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 2 * kk + g));
+                    u.q[1] = make_uint4(0, 0, 0, 0);
+                } else {
+                    u.q[0] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 4 * kk + g));
+                    u.q[1] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 4 * kk + 2 + g));
                 }
-                return *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 2 * jr + g));
-            };
-            auto dec = [&](int st, int f) -> v8bf {
-                const uint4 r = raw[(st >> 1) & 1][f];
-                const int t = st & 1;
-                if (f < MI)
-                    return P4 ? decode8<PKIND>(t ? r.y : r.x, 0u, pf) : decode8<PKIND>(t ? r.z : r.x, t ? r.w : r.y, pf);
-                return Q4 ? decode8<QKIND>(t ? r.y : r.x, 0u, qf) : decode8<QKIND>(t ? r.z : r.x, t ? r.w : r.y, qf);
-            };
-#pragma unroll
-            for (int f = 0; f < NF; ++f) raw[0][f] = lds_read(0, f);
-#pragma unroll
-            for (int f = 0; f < NF; ++f) frag[0][f] = dec(0, f);
-#pragma unroll
-            for (int st = 0; st < 8; ++st) {
-#pragma unroll
-                for (int k = 0; k < NM; ++k) {
-                    const int i = k / NI, jj = k - i * NI;
-                    acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[st & 1][i], frag[st & 1][MI + jj], acc[i][jj],
-                                                                        0, 0, 0);
-#pragma unroll
-                    for (int f = k; f < NF; f += NM) {
-                        if ((st & 1) == 0 && st < 6) raw[((st >> 1) + 1) & 1][f] = lds_read((st >> 1) + 1, f);
-                        if (st < 7) frag[(st + 1) & 1][f] = dec(st + 1, f);
-                    }
-                    // the loads of the step two ahead: one every third slot
-                    if ((st * NM + k) % 3 == 2 && (st * NM + k) / 3 < LOADS) issue_one((st * NM + k) / 3, to_stage);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+                qfr[i] = u.v;
             }
-            static_assert(3 * LOADS <= 8 * NM, "not enough slots for the loads");
-        } else {
 #pragma unroll
-            for (int idx = 0; idx < LOADS; ++idx) issue_one(idx, to_stage);
-            // Two 64-code MFMA steps.  The instruction pairs byte i < 16 of an 8-bit operand (lane half g)
-            // with K index 16g + i and byte 16 + i with 32 + 16g + i, and nibble i of a 4-bit operand with
-            // K index 32g + i; the chunk choices follow from that.
+            for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                v8i pfr[MI], qfr[NI];
-#pragma unroll
-                for (int i = 0; i < MI; ++i) {
-                    const int row = prow0 + 32 * i;
-                    union { v8i v; uint4 q[2]; } u;
-                    if (P4) {
-                        u.q[0] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 2 * kk + g));
-                        u.q[1] = make_uint4(0, 0, 0, 0);
-                    } else {
-                        u.q[0] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 4 * kk + g));
-                        u.q[1] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 4 * kk + 2 + g));
-                    }
-                    pfr[i] = u.v;
-                }
-#pragma unroll
-                for (int i = 0; i < NI; ++i) {
-                    const int row = qrow0 + 32 * i;
-                    union { v8i v; uint4 q[2]; } u;
-                    if (Q4) {
-                        u.q[0] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 2 * kk + g));
-                        u.q[1] = make_uint4(0, 0, 0, 0);
-                    } else {
-                        u.q[0] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 4 * kk + g));
-                        u.q[1] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 4 * kk + 2 + g));
-                    }
-                    qfr[i] = u.v;
-                }
-#pragma unroll
-                for (int i = 0; i < MI; ++i)
-#pragma unroll
-                    for (int jj = 0; jj < NI; ++jj)
-                        acc[i][jj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pfr[i], qfr[jj], acc[i][jj], PFMT, QFMT,
-                                                                                   0, 0, 0, 0);
-            }
+                for (int jj = 0; jj < NI; ++jj)
+                    acc[i][jj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pfr[i], qfr[jj], acc[i][jj], PFMT, QFMT,
+                                                                               0, 0, 0, 0);
         }
     };
 
     // ---- epilogue of one work item: acc * (sx * alpha * sw[n]) + bias[n].
     // P = activations (accumulator registers run along m), Q = weights (lanes run along n), so the scale
-    // and bias of a lane depend only on the column block j: they are fetched before the K loop of the item.
-    // Row-major [M, N] output: the 32 lanes of a half-wave store 128 consecutive bytes.  NCHW output: the
-    // four registers of a lane are four consecutive pixels, one 16-byte store.
+    // and bias of a lane depend only on the column block j.  The BW scales and biases of a work item are
+    // fetched into LDS (behind the ring, two alternating slots) by two loads of the same kind as the tile
+    // loads, issued by every wave when the item starts: they retire in order with the tile loads, so no
+    // wait of their own is needed before the K loop, and a missing bias (or a K slice other than the first)
+    // is an out-of-range offset, which reads as zero.
     const float sxa = (a.sx_dev ? a.sx_dev[0] : a.sx) * a.alpha;
-    float sc[NI], bv[NI];
-    auto epilogue_setup = [&](int n0, int sl) {
-#pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int n = min(n0 + 32 * j + l32, a.N - 1);
-            sc[j] = sxa * a.sw[n];
-            bv[j] = (a.bias && sl == 0) ? a.bias[n] : 0.0f;
-            // keep the values in registers across the K loop (otherwise the loads are re-issued, and
-            // waited for, at every use in the epilogue)
-            asm volatile("" : "+v"(sc[j]), "+v"(bv[j]));
-        }
+    constexpr int RING = NSTAGE * STAGE;
+    const v4i swrsrc = make_rsrc(a.sw, (unsigned)a.N * 4u);
+    const v4i brsrc = make_rsrc(a.bias, a.bias ? (unsigned)a.N * 4u : 0u);
+    auto issue_scales = [&](int n0, int sl, int par) {
+        const unsigned off = lane < BW / 4 ? (unsigned)(n0 * 4 + lane * 16) : OOB;
+        dma16(swrsrc, off, lds0 + RING + par * 2048);
+        dma16(brsrc, sl == 0 ? off : OOB, lds0 + RING + par * 2048 + 1024);
     };
-    auto epilogue = [&](int m0, int n0, int sl) {
+    // Whole tiles take the fast path: a 4 x 4 transpose inside each quad of lanes (two DPP exchange steps)
+    // turns "lane = output channel, 4 registers = 4 consecutive rows / pixels" into a layout in which
+    // eight neighbouring lanes together hold 128 consecutive output bytes, so that every store
+    // instruction writes whole cache lines, 16 bytes per lane:
+    //   row-major [M, N]: the four registers r % 4 (rows) swap with the lane's position b in its quad
+    //     (columns): afterwards lane (a, b) holds row 8 q + 4 g + b, columns 4 a .. 4 a + 3;
+    //   NCHW: the four register groups q (pixels 8 q + 4 g .. + 3) swap with b (channels): afterwards
+    //     lane (a, b) holds, in group q, channel 4 a + q and pixels 8 b + 4 g .. + 3.
+    // Either way the scale and bias of the lane's values are the four entries 4 a .. 4 a + 3 of the
+    // column block.  Returns true when the stores issued are exactly SFULL instructions.
+    auto epilogue = [&](int m0, int n0, int sl, int par) -> bool {
+        const float* stab = reinterpret_cast<const float*>(smem + RING + par * 2048);
         // split-K: slice s writes its scaled partial sums to partial[s]; a second kernel adds the slices
         float* const yout = a.splits > 1 ? a.partial + (size_t)sl * ((size_t)a.M * a.N) : a.y;
         const bool full = (m0 + BX <= a.M) && (n0 + BW <= a.N);   // whole tile inside the output
         const int mw = m0 + wave * TX;                           // first row of this wave
-        if constexpr (!CONV) {
-            const unsigned lane_off = (unsigned)(4 * g * a.N + l32);
-            if (full) {
+        const int hw = CONV ? a.Ho * a.Wo : 4;
+        const bool vec = full && ((hw & 3) == 0) && ((reinterpret_cast<uintptr_t>(yout) & 15) == 0);
+        if (vec) {
+            const int qa = l32 >> 2, qb = l32 & 3;
+            const bool b0 = qb & 1, b1 = qb & 2;
+            float4 sc4[NI], bv4[NI];
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const float4 s4 = *reinterpret_cast<const float4*>(stab + 32 * j + 4 * qa);
+                sc4[j] = make_float4(s4.x * sxa, s4.y * sxa, s4.z * sxa, s4.w * sxa);
+                bv4[j] = *reinterpret_cast<const float4*>(stab + 256 + 32 * j + 4 * qa);
+            }
+            if constexpr (!CONV) {
+                // row-major output keeps the plain layout: 32 lanes store 128 consecutive bytes of one row
+                // (measured faster than 16-byte stores spread over eight rows)
+                const unsigned lane_off = (unsigned)(4 * g * a.N + l32);
+                float sc[NI], bv[NI];
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    sc[j] = sxa * stab[32 * j + l32];
+                    bv[j] = stab[256 + 32 * j + l32];
+                }
 #pragma unroll
                 for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -372,61 +469,69 @@ __global__ __launch_bounds__(256, (BX <= 128 ? 2 : 1)) void gemm_dma_kernel(cons
                     }
             } else {
 #pragma unroll
-                for (int i = 0; i < MI; ++i)
+                for (int i = 0; i < MI; ++i) {
+                    const int m = mw + 32 * i + 8 * qb + 4 * g;   // hw % 4 == 0: the four pixels lie in one image
+                    const int bi = m / hw;
+                    const int pix = m - bi * hw;
+                    float* mp = yout + ((size_t)bi * a.N + n0 + 4 * qa) * hw + pix;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int m = mw + 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
-#pragma unroll
-                        for (int j = 0; j < NI; ++j) {
-                            const int n = n0 + 32 * j + l32;
-                            if (m < a.M && n < a.N) yout[(size_t)m * a.N + n] = acc[i][j][r] * sc[j] + bv[j];
-                        }
-                    }
-            }
-        } else {
-            const int hw = a.Ho * a.Wo;
-            const bool vec = full && ((hw & 3) == 0) && ((reinterpret_cast<uintptr_t>(yout) & 15) == 0);
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    const int m = mw + 32 * i + 8 * q4 + 4 * g;
-                    if (vec) {   // hw % 4 == 0: the four pixels lie in one image
-                        const int bi = m / hw;
-                        const int pix = m - bi * hw;
-                        float* mp = yout + (size_t)bi * a.N * hw + pix + (size_t)(n0 + l32) * hw;
-#pragma unroll
-                        for (int j = 0; j < NI; ++j)
-                            *reinterpret_cast<float4*>(mp + (size_t)(32 * j) * hw) =
-                                make_float4(acc[i][j][4 * q4 + 0] * sc[j] + bv[j], acc[i][j][4 * q4 + 1] * sc[j] + bv[j],
-                                            acc[i][j][4 * q4 + 2] * sc[j] + bv[j], acc[i][j][4 * q4 + 3] * sc[j] + bv[j]);
-                    } else {
+                    for (int j = 0; j < NI; ++j) {
+                        float v[4][4];   // [pixel e][group q]
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            if (m + e >= a.M) continue;
-                            const int bi = (m + e) / hw;
-                            const int pix = (m + e) - bi * hw;
 #pragma unroll
-                            for (int j = 0; j < NI; ++j) {
-                                const int n = n0 + 32 * j + l32;
-                                if (n < a.N) yout[((size_t)bi * a.N + n) * hw + pix] = acc[i][j][4 * q4 + e] * sc[j] + bv[j];
-                            }
+                            for (int q4 = 0; q4 < 4; ++q4) v[e][q4] = acc[i][j][4 * q4 + e];
+                            quad_transpose(v[e], b0, b1);
                         }
+                        const float scq[4] = {sc4[j].x, sc4[j].y, sc4[j].z, sc4[j].w};
+                        const float bvq[4] = {bv4[j].x, bv4[j].y, bv4[j].z, bv4[j].w};
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4)
+                            *reinterpret_cast<float4*>(mp + (size_t)(32 * j + q4) * hw) =
+                                make_float4(v[0][q4] * scq[q4] + bvq[q4], v[1][q4] * scq[q4] + bvq[q4],
+                                            v[2][q4] * scq[q4] + bvq[q4], v[3][q4] * scq[q4] + bvq[q4]);
                     }
                 }
+            }
+            return true;
         }
+        // tiles that cross the edge of the output, or an output that does not allow 16-byte stores
+        float sc[NI], bv[NI];
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            sc[j] = sxa * stab[32 * j + l32];
+            bv[j] = stab[256 + 32 * j + l32];
+        }
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = mw + 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
+                if (m >= a.M) continue;
+                size_t base;
+                size_t nstride;
+                if (CONV) {
+                    const int bi = m / hw;
+                    base = (size_t)bi * a.N * hw + (m - bi * hw);
+                    nstride = (size_t)hw;
+                } else {
+                    base = (size_t)m * a.N;
+                    nstride = 1;
+                }
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    const int n = n0 + 32 * j + l32;
+                    if (n < a.N) yout[base + (size_t)n * nstride] = acc[i][j][r] * sc[j] + bv[j];
+                }
+            }
+        return false;
     };
 
     // ---- main loop over the K steps of all work items of this workgroup.  Each wave issues LOADS buffer
     // loads per step and they complete in order.  The loads run NSTAGE - 1 steps ahead of the MFMAs,
-    // across item boundaries.  On entry to a step the wave's outstanding loads are the NSTAGE - 1 groups
-    // issued last, so vmcnt <= LOADS * (NSTAGE - 2) means the oldest of them, this step's, has landed; the barrier then says the same of every wave, and that every wave has finished reading the
-    // ring slot of the previous step, which the loads issued during this step overwrite.  The stores of an epilogue also
-    // count in vmcnt and are not ordered against loads, so the first wait after an epilogue drains
-    // everything (vmcnt 0).
-    // Every step issues one group of LOADS loads, NSTAGE - 1 steps ahead of its use; once the work items
-    // run out the group is a dummy (every offset out of range: zeros into a free ring slot, no memory
-    // traffic), which keeps the control flow and the vmcnt arithmetic uniform.
+    // across item boundaries.  Every step issues one group of LOADS loads; once the work items run out
+    // the group is a dummy (every offset out of range: zeros into a free ring slot, no memory traffic),
+    // which keeps the control flow and the vmcnt arithmetic uniform.
     int istage = 0;
     ihas = i_item < nitems;
     if (ihas) issue_setup();
@@ -458,33 +563,74 @@ __global__ __launch_bounds__(256, (BX <= 128 ? 2 : 1)) void gemm_dma_kernel(cons
     }
 
     int cstage = 0;
-    bool drain = false;
-    for (int c_item = q; c_item < nitems; c_item += G) {
-        const int tile = c_item / a.splits, sl = c_item - tile * a.splits;
-        const int tx = tile / tiles_w, tw = tile - tx * tiles_w;
-        const int nk = (int)((long)nk_all * (sl + 1) / a.splits) - (int)((long)nk_all * sl / a.splits);
-        epilogue_setup(tw * BW, sl);
-        for (int kt = 0; kt < nk; ++kt) {
-            if (NSTAGE == 3 && !drain)
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(LOADS));
-            else
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-            drain = false;
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-            compute(cstage, istage);   // the loads of the step NSTAGE - 1 ahead ride along with the MFMAs
-            issued();
-            cstage = (cstage + 1 == NSTAGE) ? 0 : cstage + 1;
-        }
-        epilogue(tx * BX, tw * BW, sl);
-        drain = true;
+    int par = 0;
+    auto clear_acc = [&]() {
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int j = 0; j < NI; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    };
+    if constexpr (ACC == FPQ_ACC_FP32) {
+        // the first ring slot: its group is the oldest of the NSTAGE - 1 outstanding ones
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(LOADS * (NSTAGE - 2)));
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        first_fragments(0);
+        int mode = W_FIRST;
+        for (int c_item = q; c_item < nitems; c_item += G) {
+            const int tile = c_item / a.splits, sl = c_item - tile * a.splits;
+            const int tx = tile / tiles_w, tw = tile - tx * tiles_w;
+            const int nk = (int)((long)nk_all * (sl + 1) / a.splits) - (int)((long)nk_all * sl / a.splits);
+            issue_scales(tw * BW, sl, par);
+            for (int kt = 0; kt < nk; ++kt) {
+                const int nstage = (cstage + 1 == NSTAGE) ? 0 : cstage + 1;
+                compute(cstage, nstage, istage, mode);
+                mode = W_NORMAL;
+                issued();
+                cstage = nstage;
+            }
+            // the scale loads are older than the loads issued during the item's K steps (at least one group)
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(LOADS));
+            asm volatile("" ::: "memory");
+            mode = epilogue(tx * BX, tw * BW, sl, par) ? W_AFTER_STORES : W_DRAIN;
+            par ^= 1;
+            clear_acc();
+        }
+    } else {
+        // On entry to a step the wave's outstanding loads are the NSTAGE - 1 groups issued last, so
+        // vmcnt <= LOADS * (NSTAGE - 2) means the oldest of them, this step's, has landed (the two scale
+        // loads of an item only make the wait stricter); the barrier then says the same of every wave, and
+        // that every wave has finished reading the ring slot of the previous step, which the loads issued
+        // during this step overwrite.  The first wait after an epilogue drains its stores as well.
+        bool drain = false;
+        for (int c_item = q; c_item < nitems; c_item += G) {
+            const int tile = c_item / a.splits, sl = c_item - tile * a.splits;
+            const int tx = tile / tiles_w, tw = tile - tx * tiles_w;
+            const int nk = (int)((long)nk_all * (sl + 1) / a.splits) - (int)((long)nk_all * sl / a.splits);
+            issue_scales(tw * BW, sl, par);
+            for (int kt = 0; kt < nk; ++kt) {
+                if (NSTAGE == 3 && !drain)
+                    __builtin_amdgcn_s_waitcnt(vmcnt_imm(LOADS));
+                else
+                    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                drain = false;
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                compute8(cstage, istage);   // the loads of the step NSTAGE - 1 ahead are issued first
+                issued();
+                cstage = (cstage + 1 == NSTAGE) ? 0 : cstage + 1;
+            }
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(LOADS));
+            asm volatile("" ::: "memory");
+            epilogue(tx * BX, tw * BW, sl, par);
+            par ^= 1;
+            drain = true;
+            clear_acc();
+        }
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // no load may land in LDS after the workgroup has gone
 }
@@ -518,7 +664,7 @@ template <int BX, int BW, int NSTAGE, int XKIND, int WKIND, int ACC, bool CONV>
 static int launch_dma_one(const GemmArgs& a, hipStream_t st)
 {
     constexpr int WROWB = kind_is_4bit(WKIND) ? 64 : 128;
-    constexpr int smem = NSTAGE * (BX * 128 + (BW * WROWB + 4095) / 4096 * 4096);
+    constexpr int smem = NSTAGE * (BX * 128 + (BW * WROWB + 4095) / 4096 * 4096) + 4096;   // ring + scale / bias slots
     const int tiles = ((a.M + BX - 1) / BX) * ((a.N + BW - 1) / BW);
     auto kern = gemm_dma_kernel<BX, BW, NSTAGE, XKIND, WKIND, ACC, CONV>;
     static bool raised = false;   // per instantiation

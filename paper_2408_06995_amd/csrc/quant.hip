@@ -26,6 +26,21 @@ __device__ __forceinline__ float block_max(float v)
     return v;
 }
 
+// r = fl32(1 / scale) for a quantize kernel (all threads of the block call this).
+__device__ __forceinline__ float block_inv_scale(const ScaleSrc& s)
+{
+    if (s.partials == nullptr) return inv_scale(s.host, s.dev);
+    float v = 0.0f;
+    for (int i = threadIdx.x; i < s.nparts; i += 256) v = fmaxf(v, s.partials[i]);
+    v = block_max(v);
+    const float sc = (v == 0.0f) ? 1.0f : __fdiv_rn(v, s.maxval);
+    if (s.publish && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) {
+        s.publish[0] = sc;
+        s.publish[1] = v;
+    }
+    return __fdiv_rn(1.0f, sc);
+}
+
 // Pass 1: each block folds a grid-strided share of x into one partial maximum of |x|.
 __global__ __launch_bounds__(256) void absmax_partial_kernel(const float* __restrict__ x, size_t n,
                                                              float* __restrict__ partial)
@@ -81,16 +96,23 @@ int launch_absmax(const float* x, size_t n, float maxval, float* absmax_out, flo
     return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
 }
 
+// Pass 1 alone, for the dynamic-scale path of the layer entry points (the quantize kernel folds the partials).
+int launch_absmax_partials(const float* x, size_t n, float* partial, hipStream_t st)
+{
+    const int nparts = absmax_parts(n);
+    if (nparts > 0) hipLaunchKernelGGL(absmax_partial_kernel, dim3(nparts), dim3(256), 0, st, x, n, partial);
+    return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
+}
+
 // ------------------------------------------------------------------------------ quantize (flat)
 
 // Four elements per lane and step: one 16-byte load, four encodes, one 4-byte (8-bit codes) or
 // 2-byte (4-bit codes) store.  Four independent loads are kept in flight per lane.
 template <bool FOUR_BIT>
 __global__ __launch_bounds__(256) void quantize_vec_kernel(const float4* __restrict__ x4, size_t n4, QParams q,
-                                                           float scale, const float* __restrict__ scale_dev,
-                                                           uint8_t* __restrict__ codes)
+                                                           ScaleSrc ss, uint8_t* __restrict__ codes)
 {
-    const float r = inv_scale(scale, scale_dev);
+    const float r = block_inv_scale(ss);
     const size_t nthreads = (size_t)gridDim.x * 256;
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     auto emit = [&](size_t idx, const float4& v) {
@@ -114,11 +136,10 @@ __global__ __launch_bounds__(256) void quantize_vec_kernel(const float4* __restr
 // One output byte per lane: any alignment, tails.  first = index of the first element handled.
 template <bool FOUR_BIT>
 __global__ __launch_bounds__(256) void quantize_scalar_kernel(const float* __restrict__ x, size_t first, size_t n,
-                                                              QParams q, float scale,
-                                                              const float* __restrict__ scale_dev,
+                                                              QParams q, ScaleSrc ss,
                                                               uint8_t* __restrict__ codes)
 {
-    const float r = inv_scale(scale, scale_dev);
+    const float r = block_inv_scale(ss);
     const size_t per = FOUR_BIT ? 2 : 1;
     size_t j = first / per + (size_t)blockIdx.x * 256 + threadIdx.x;  // output byte
     const size_t nbytes = (n + per - 1) / per;
@@ -142,8 +163,8 @@ static int grid_for(size_t work_items, int per_block)
     return (int)g;
 }
 
-int launch_quantize(const float* x, size_t n, const QParams& q, bool four_bit, float scale,
-                    const float* scale_dev, uint8_t* codes, hipStream_t st)
+int launch_quantize(const float* x, size_t n, const QParams& q, bool four_bit, const ScaleSrc& ss, uint8_t* codes,
+                    hipStream_t st)
 {
     if (n == 0) return FPQ_OK;
     bool aligned = (reinterpret_cast<uintptr_t>(x) & 15) == 0 && (reinterpret_cast<uintptr_t>(codes) & 3) == 0;
@@ -152,20 +173,18 @@ int launch_quantize(const float* x, size_t n, const QParams& q, bool four_bit, f
         int g = grid_for(n4, 256 * 4);
         if (four_bit)
             hipLaunchKernelGGL(quantize_vec_kernel<true>, dim3(g), dim3(256), 0, st,
-                               reinterpret_cast<const float4*>(x), n4, q, scale, scale_dev, codes);
+                               reinterpret_cast<const float4*>(x), n4, q, ss, codes);
         else
             hipLaunchKernelGGL(quantize_vec_kernel<false>, dim3(g), dim3(256), 0, st,
-                               reinterpret_cast<const float4*>(x), n4, q, scale, scale_dev, codes);
+                               reinterpret_cast<const float4*>(x), n4, q, ss, codes);
     }
     size_t first = n4 << 2;
     if (first < n) {
         int g = grid_for(n - first, 256);
         if (four_bit)
-            hipLaunchKernelGGL(quantize_scalar_kernel<true>, dim3(g), dim3(256), 0, st, x, first, n, q, scale,
-                               scale_dev, codes);
+            hipLaunchKernelGGL(quantize_scalar_kernel<true>, dim3(g), dim3(256), 0, st, x, first, n, q, ss, codes);
         else
-            hipLaunchKernelGGL(quantize_scalar_kernel<false>, dim3(g), dim3(256), 0, st, x, first, n, q, scale,
-                               scale_dev, codes);
+            hipLaunchKernelGGL(quantize_scalar_kernel<false>, dim3(g), dim3(256), 0, st, x, first, n, q, ss, codes);
     }
     return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
 }
@@ -177,13 +196,12 @@ int launch_quantize(const float* x, size_t n, const QParams& q, bool four_bit, f
 // Channels C..Cp-1 receive code 0.  Rows of the tile are 68 bytes so that the four-byte column
 // groups of neighbouring pixels fall into different LDS banks.
 __global__ __launch_bounds__(256) void quantize_nhwc_kernel(const float* __restrict__ x, int C, int Cp, int HW,
-                                                            QParams q, float scale,
-                                                            const float* __restrict__ scale_dev,
+                                                            QParams q, ScaleSrc ss,
                                                             uint8_t* __restrict__ codes)
 {
     constexpr int LDW = 68;
     __shared__ __attribute__((aligned(16))) uint8_t tile[64 * LDW];
-    const float r = inv_scale(scale, scale_dev);
+    const float r = block_inv_scale(ss);
     const int b = blockIdx.z;
     const int c0 = blockIdx.y * 64;
     const int p0 = blockIdx.x * 64;
@@ -226,12 +244,12 @@ __global__ __launch_bounds__(256) void quantize_nhwc_kernel(const float* __restr
 }
 
 int launch_quantize_nhwc(const float* x, int64_t B, int64_t C, int64_t H, int64_t W, const QParams& q,
-                         float scale, const float* scale_dev, uint8_t* codes, hipStream_t st)
+                         const ScaleSrc& ss, uint8_t* codes, hipStream_t st)
 {
     int Cp = (int)padded_channels(C);
     int HW = (int)(H * W);
     dim3 grid((HW + 63) / 64, (Cp + 63) / 64, (unsigned)B);
-    hipLaunchKernelGGL(quantize_nhwc_kernel, grid, dim3(256), 0, st, x, (int)C, Cp, HW, q, scale, scale_dev, codes);
+    hipLaunchKernelGGL(quantize_nhwc_kernel, grid, dim3(256), 0, st, x, (int)C, Cp, HW, q, ss, codes);
     return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
 }
 

@@ -57,9 +57,9 @@ def test_sizes():
     assert B.fpq_code_bytes(10, synth.E4M3) == 10
     assert B.fpq_code_bytes(11, synth.E2M1) == 6
     assert B.fpq_padded_channels(4) == 16 and B.fpq_padded_channels(320) == 320
-    assert B.fpq_packed_size(320, 320, 1, 1, synth.E4M3) == 64 + 320 * 384
-    assert B.fpq_packed_size(320, 320, 3, 3, synth.E4M3) == 64 + 320 * 2944
-    assert B.fpq_packed_size(1280, 1280, 3, 3, synth.E2M1) == 64 + 1280 * 11520 // 2
+    assert B.fpq_packed_size(320, 320, 1, 1, synth.E4M3) == 256 + 320 * 384
+    assert B.fpq_packed_size(320, 320, 3, 3, synth.E4M3) == 256 + 320 * 2944
+    assert B.fpq_packed_size(1280, 1280, 3, 3, synth.E2M1) == 256 + 1280 * 11520 // 2
     assert B.fpq_packed_size(0, 320, 1, 1, synth.E4M3) == 0
     assert B.fpq_absmax_workspace_size(0) == 4 and B.fpq_absmax_workspace_size(10 ** 9) == 4096
     assert B.fpq_gemm_workspace_size(256, 320, 320, 0) == 0
@@ -95,6 +95,9 @@ def test_argument_validation_without_gpu():
     assert L.fpq_gemm(p, 0, f, -1.0, None, p, f, p, None, p, 8, 8, 32, 0, None, 0, None) == -3
     assert L.fpq_gemm(p, 0, f, 1.0, None, p, f, p, None, p, 8, 8, 24, 0, None, 0, None) == -5
     assert L.fpq_gemm(p, 1, f, 1.0, None, p, f, p, None, p, 8, 8, 32, 0, None, 0, None) == -6
+    assert L.fpq_gemm(p, 2, f, 0.0, None, p, f, p, None, p, 8, 8, 32, 0, None, 0, None) == -6   # dynamic scale: no sx needed
+    assert L.fpq_gemm(p, 3, f, 1.0, None, p, f, p, None, p, 8, 8, 32, 0, None, 0, None) == -8
+    assert B.fpq_gemm_workspace_size(8, 8, 32, 2) == B.fpq_gemm_workspace_size(8, 8, 32, 1) + 4096 + 256
     assert L.fpq_gemm(p, 0, e2m1, 1.0, None, p, f, p, None, p, 8, 8, 32, 0, None, 0, None) == -8
     assert L.fpq_gemm(p, 0, B.fmt(synth.E3M4), 1.0, None, p, f, p, None, p, 8, 8, 32, 1, None, 0, None) == -8
     assert L.fpq_gemm(p, 0, f, 1.0, None, p, f, p, None, p, 8, 8, 32, 7, None, 0, None) == -8

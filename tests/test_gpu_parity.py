@@ -328,6 +328,58 @@ def test_conv_fp32_input_equals_codes_input():
     assert np.array_equal(y0, y1)
 
 
+@pytest.mark.parametrize("shape", [("linear", 256, 320, 320), ("linear", 9, 40, 17), ("linear", 2048, 1280, 320),
+                                   ("conv", 2, 20, 9, 9, 24, 3, 1), ("conv", 1, 320, 32, 32, 320, 3, 1),
+                                   ("conv", 2, 64, 16, 16, 160, 1, 2)])
+def test_dynamic_scale_entry_equals_absmax_then_quantize(shape):
+    """x_is_fp32 == 2: the scale absmax / maxval found inside the call gives the same codes, hence the same
+    outputs bit for bit, as fpq_absmax followed by the fp32 entry with that device scale; and the result
+    is the oracle's for the oracle's own absmax scale."""
+    fx, fw = synth.E4M3, synth.E2M1
+    if shape[0] == "linear":
+        _, M, K, N = shape
+        x = synth.activations((M, K), 11)
+        w = synth.weights((N, K), 12)
+    else:
+        _, Bn, Cin, H, W, Cout, k, stride = shape
+        x = synth.activations((Bn, Cin, H, W), 11)
+        w = synth.weights((Cout, Cin, k, k), 12)
+    x[0].flat[3] = -37.5    # the absmax element is negative
+    h = synth.rounding_mask(w.shape, 13)
+    packed, sw_t, wq = gpu_pack(w, fw, h)
+    xd = dev(x)
+    stat = torch.empty(2, dtype=torch.float32, device=DEV)
+    tmp = torch.empty(1024, dtype=torch.float32, device=DEV)
+    B.fpq_absmax(xd, fx[3], stat[0:1], stat[1:2], tmp)
+    ys = []
+    for mode in (1, 2):
+        if shape[0] == "linear":
+            y = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+            ws = torch.empty(B.fpq_gemm_workspace_size(M, N, K, mode), dtype=torch.uint8, device=DEV)
+            B.fpq_gemm(xd, mode, fx, 0.0, stat[1:2] if mode == 1 else None, packed, fw, sw_t, None, y, M, N, K,
+                       B.FPQ_ACC_FP32, ws)
+        else:
+            pad = k // 2
+            Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+            y = torch.full((Bn, Cout, Ho, Wo), float("nan"), dtype=torch.float32, device=DEV)
+            ws = torch.empty(B.fpq_conv2d_workspace_size(Bn, Cin, H, W, Cout, k, k, stride, pad, mode), dtype=torch.uint8,
+                             device=DEV)
+            B.fpq_conv2d(xd, mode, fx, 0.0, stat[1:2] if mode == 1 else None, packed, fw, sw_t, None, y, Bn, Cin, H, W,
+                         Cout, k, k, stride, pad, B.FPQ_ACC_FP32, ws)
+        torch.cuda.synchronize()
+        ys.append(y.cpu().numpy())
+    assert np.array_equal(ys[0], ys[1])
+    sx = oracle.scale_from_absmax(oracle.absmax(x), fx[3])
+    assert sx == float(stat[1].item())
+    xq = oracle.quantize(x, fx, sx)
+    sw = sw_t.cpu().numpy()
+    if shape[0] == "linear":
+        Y, T = oracle.gemm(xq, fx, sx, wq, fw, sw)
+    else:
+        Y, T = oracle.conv2d(xq, fx, sx, wq, fw, sw, stride=stride, pad=k // 2)
+    check_close(ys[1], Y, T, what="dynamic scale %s" % (shape,))
+
+
 def test_conv_one_hot_taps_exact():
     """One non-zero input pixel and one non-zero weight tap: the output is a single 1 at the shifted position."""
     fx = fw = synth.E4M3
