@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--acc", default="fp32", choices=["fp32", "fp8mfma"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the quantize-bandwidth probe and the other acc mode")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy (the known-size kernel that hardware-counter "
+                         "readings of a profiler run are scaled by)")
     return ap.parse_args()
 
 
@@ -152,6 +155,13 @@ def main():
             graph.replay()
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
+
+    if args.copy_calibration:
+        src = torch.ones(64 << 20, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     sec = timed(acc, args.steps, args.warmup)
 

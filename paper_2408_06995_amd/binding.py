@@ -9,7 +9,7 @@ import ctypes as C
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libfpq.so")
+LIB_PATH = os.environ.get("FPQ_LIB_PATH") or os.path.join(HERE, "libfpq.so")   # FPQ_LIB_PATH: a library built elsewhere
 
 FPQ_ACC_FP32 = 0
 FPQ_ACC_FP8_MFMA = 1

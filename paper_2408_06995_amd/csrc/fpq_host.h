@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "../../include/fpq.h"
 
@@ -82,7 +83,8 @@ struct GemmArgs {
 enum GemmTile : int {
     TILE_GENERIC = 0,    // register-staged 128x128 / 64x64 kernels: any shape
     TILE_256x160_S3 = 1, // LDS-DMA kernel, three stages: deep K
-    TILE_128x160_S2 = 2  // LDS-DMA kernel, two stages, two workgroups per compute unit: short K
+    TILE_128x160_S2 = 2, // LDS-DMA kernel, two stages, two workgroups per compute unit
+    TILE_128x160_S4 = 3  // LDS-DMA kernel, four stages, one workgroup per compute unit (FPQ_ACC_FP32 only)
 };
 struct GemmPlan {
     int tile;
@@ -92,30 +94,49 @@ struct GemmPlan {
 // The large-tile kernels need N to be a multiple of 160 (every U-Net width, a multiple of 320, is).
 // Deep K with enough 256-row tiles to fill the compute units takes the 256 x 160 tile with three
 // stages (one workgroup per compute unit); everything else takes the 128 x 160 tile with two stages,
-// of which two workgroups fit on a compute unit and overlap each other's load and store phases.
-// When the tile grid alone would leave a quarter of the compute units idle, K is cut into slices: aim
-// at a little more than one workgroup per compute unit, keep at least 4 K steps per slice and at most
-// 256 MB of partial results (each split costs a reduction launch and a round trip of the partials).
+// of which two workgroups fit on a compute unit.  When the tile grid alone would leave compute units
+// idle and K is deep, K is cut into slices (each split costs a reduction launch and a round trip of
+// the partial sums, which only a deep K pays back): 2 to 4 slices of the 256-row tile when that gives
+// about one work item per compute unit with at least 32 K steps each, otherwise about two work items
+// per compute unit of the 128-row tile with at least 8 K steps each.  Problems of a few tiles and a
+// short K are bound by the length of their serial K loop and are sliced as well.  At most 256 MB of
+// partial sums.
 static inline GemmPlan plan_gemm(int64_t M, int64_t N, int64_t Kpad)
 {
     GemmPlan p{TILE_GENERIC, 1};
     if (N % 160 != 0 || M < 1) return p;
+#ifdef FPQ_TUNING   // tuning builds only: FPQ_FORCE_TILE / FPQ_FORCE_SPLITS override the plan, for sweeps
+    if (const char* ft = getenv("FPQ_FORCE_TILE")) {
+        p.tile = atoi(ft);
+        const char* fs = getenv("FPQ_FORCE_SPLITS");
+        p.splits = fs ? atoi(fs) : 1;
+        const int64_t nkk = Kpad / 128;
+        if (p.splits > nkk) p.splits = (int)nkk;
+        return p;
+    }
+#endif
     const int64_t nk = Kpad / 128;
     const int64_t tiles256 = ((M + 255) / 256) * (N / 160);
+    const int64_t tiles = ((M + 127) / 128) * (N / 160);
+    int64_t s = 1;
     if (nk >= 16 && tiles256 >= 192) {
         p.tile = TILE_256x160_S3;
         return p;
     }
     p.tile = TILE_128x160_S2;
-    const int64_t tiles = ((M + 127) / 128) * (N / 160);
-    if (tiles < 192 && nk >= 8) {
-        int64_t s = (320 + tiles - 1) / tiles;
-        if (s > nk / 4) s = nk / 4;
+    if (tiles256 < 192 && tiles256 >= 48 && nk >= 32 * ((256 + tiles256 / 2) / tiles256)) {
+        p.tile = TILE_256x160_S3;
+        s = (256 + tiles256 / 2) / tiles256;
+    } else if (tiles < 192 && nk >= 16) {
+        s = (512 + tiles / 2) / tiles;
+        if (s > nk / 8) s = nk / 8;
         if (s > 32) s = 32;
-        while (s > 1 && s * M * N * 4 > ((int64_t)256 << 20)) --s;
-        if (s < 1) s = 1;
-        p.splits = (int)s;
+    } else if (tiles <= 16 && nk >= 4) {
+        s = nk / 2 < 8 ? nk / 2 : 8;
     }
+    while (s > 1 && s * M * N * 4 > ((int64_t)256 << 20)) --s;
+    if (s < 1) s = 1;
+    p.splits = (int)s;
     return p;
 }
 static inline size_t split_workspace_bytes(const GemmPlan& p, int64_t M, int64_t N)

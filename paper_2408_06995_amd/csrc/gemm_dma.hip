@@ -51,6 +51,16 @@ __device__ __forceinline__ v4i make_rsrc(const void* base, unsigned bytes)
 // expcnt 6:4 and lgkmcnt 11:8 left at their maxima).
 constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
 
+typedef float v4f __attribute__((ext_vector_type(4)));
+// Results leave with streaming (non-temporal) stores: an output is far larger than the L2 and would
+// otherwise push out the operand tiles that other workgroups are about to re-read.
+__device__ __forceinline__ void store_out(float* p, float v) { __builtin_nontemporal_store(v, p); }
+__device__ __forceinline__ void store_out4(float* p, float x, float y, float z, float w)
+{
+    const v4f v = {x, y, z, w};
+    __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(p));
+}
+
 // Exchange helpers for the epilogue's 4 x 4 transpose: the value of the lane whose number differs in bit 0
 // (or bit 1) within the same quad of lanes.
 __device__ __forceinline__ float quad_xor1(float x)
@@ -81,7 +91,7 @@ __device__ __forceinline__ void quad_transpose(float (&v)[4], bool b0, bool b1)
 }
 
 template <int BX, int BW, int NSTAGE, int XKIND, int WKIND, int ACC, bool CONV>
-__global__ __launch_bounds__(256, (BX <= 128 ? 2 : 1)) void gemm_dma_kernel(const GemmArgs a)
+__global__ __launch_bounds__(256, ((BX <= 128 && NSTAGE <= 2) ? 2 : 1)) void gemm_dma_kernel(const GemmArgs a)
 {
     constexpr bool W4 = kind_is_4bit(WKIND);
     constexpr int XROWB = 128;
@@ -309,22 +319,23 @@ __global__ __launch_bounds__(256, (BX <= 128 ? 2 : 1)) void gemm_dma_kernel(cons
     // every wave's share of that ring slot is valid, and every wave has finished reading the ring slot
     // of the current step (its last LDS read was consumed an MFMA step ago), which the loads issued
     // from the next step on overwrite.  Buffer loads and stores of a wave retire in issue order, so
-    // "vmcnt <= n" means that all but the n youngest operations are complete.  Youngest operations at
-    // this point, for three stages: the LOADS loads issued during this step; in the first step of a
-    // work item before them the two scale / bias loads and the stores of the previous item's epilogue
-    // (the counter saturates at 63, hence the min).  With two stages the wanted loads are themselves
-    // the youngest, so the wait is for zero.
+    // "vmcnt <= n" means that all but the n youngest operations are complete.  Younger than the wanted
+    // group are the NSTAGE - 2 groups issued after it; and, while the wanted group still dates from
+    // before the last epilogue (the first NSTAGE - 2 steps after it), also that epilogue's stores and the
+    // two scale / bias loads of the item (the counter saturates at 63, hence the min).  With two stages
+    // the wanted loads are themselves the youngest, so the wait is for zero.
     enum { W_NORMAL = 0, W_FIRST = 1, W_AFTER_STORES = 2, W_DRAIN = 3 };
     constexpr int SFULL = CONV ? MI * 4 * NI : MI * 16 * NI;   // store instructions of the epilogue of a whole tile
+    constexpr int AHEAD = (NSTAGE - 2) * LOADS;                // loads younger than the wanted group
     auto tail_sync = [&](int mode) {
-        if (NSTAGE == 2 || mode == W_DRAIN)
+        if (mode == W_DRAIN)
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
         else if (mode == W_NORMAL)
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(LOADS));
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(AHEAD));
         else if (mode == W_FIRST)
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(LOADS + 2));
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(AHEAD + 2 < 63 ? AHEAD + 2 : 63));
         else
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(LOADS + 2 + SFULL < 63 ? LOADS + 2 + SFULL : 63));
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(AHEAD + 2 + SFULL < 63 ? AHEAD + 2 + SFULL : 63));
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
@@ -465,7 +476,7 @@ __global__ __launch_bounds__(256, (BX <= 128 ? 2 : 1)) void gemm_dma_kernel(cons
                     for (int r = 0; r < 16; ++r) {
                         float* rowp = yout + (size_t)(mw + 32 * i + 8 * (r >> 2) + (r & 3)) * a.N + n0;   // uniform
 #pragma unroll
-                        for (int j = 0; j < NI; ++j) rowp[lane_off + 32 * j] = acc[i][j][r] * sc[j] + bv[j];
+                        for (int j = 0; j < NI; ++j) store_out(rowp + lane_off + 32 * j, acc[i][j][r] * sc[j] + bv[j]);
                     }
             } else {
 #pragma unroll
@@ -487,9 +498,9 @@ __global__ __launch_bounds__(256, (BX <= 128 ? 2 : 1)) void gemm_dma_kernel(cons
                         const float bvq[4] = {bv4[j].x, bv4[j].y, bv4[j].z, bv4[j].w};
 #pragma unroll
                         for (int q4 = 0; q4 < 4; ++q4)
-                            *reinterpret_cast<float4*>(mp + (size_t)(32 * j + q4) * hw) =
-                                make_float4(v[0][q4] * scq[q4] + bvq[q4], v[1][q4] * scq[q4] + bvq[q4],
-                                            v[2][q4] * scq[q4] + bvq[q4], v[3][q4] * scq[q4] + bvq[q4]);
+                            store_out4(mp + (size_t)(32 * j + q4) * hw, v[0][q4] * scq[q4] + bvq[q4],
+                                       v[1][q4] * scq[q4] + bvq[q4], v[2][q4] * scq[q4] + bvq[q4],
+                                       v[3][q4] * scq[q4] + bvq[q4]);
                     }
                 }
             }
@@ -579,7 +590,8 @@ __global__ __launch_bounds__(256, (BX <= 128 ? 2 : 1)) void gemm_dma_kernel(cons
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         first_fragments(0);
-        int mode = W_FIRST;
+        int after = W_FIRST;   // what precedes the current item: nothing, counted stores, or uncounted stores
+        int since = 0;         // K steps since then
         for (int c_item = q; c_item < nitems; c_item += G) {
             const int tile = c_item / a.splits, sl = c_item - tile * a.splits;
             const int tx = tile / tiles_w, tw = tile - tx * tiles_w;
@@ -587,21 +599,22 @@ __global__ __launch_bounds__(256, (BX <= 128 ? 2 : 1)) void gemm_dma_kernel(cons
             issue_scales(tw * BW, sl, par);
             for (int kt = 0; kt < nk; ++kt) {
                 const int nstage = (cstage + 1 == NSTAGE) ? 0 : cstage + 1;
-                compute(cstage, nstage, istage, mode);
-                mode = W_NORMAL;
+                compute(cstage, nstage, istage, since < NSTAGE - 2 ? after : (int)W_NORMAL);
+                ++since;
                 issued();
                 cstage = nstage;
             }
             // the scale loads are older than the loads issued during the item's K steps (at least one group)
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(LOADS));
             asm volatile("" ::: "memory");
-            mode = epilogue(tx * BX, tw * BW, sl, par) ? W_AFTER_STORES : W_DRAIN;
+            after = epilogue(tx * BX, tw * BW, sl, par) ? W_AFTER_STORES : W_DRAIN;
+            since = 0;
             par ^= 1;
             clear_acc();
         }
     } else {
         // On entry to a step the wave's outstanding loads are the NSTAGE - 1 groups issued last, so
-        // vmcnt <= LOADS * (NSTAGE - 2) means the oldest of them, this step's, has landed (the two scale
+        // vmcnt <= AHEAD = LOADS * (NSTAGE - 2) means the oldest of them, this step's, has landed (the two scale
         // loads of an item only make the wait stricter); the barrier then says the same of every wave, and
         // that every wave has finished reading the ring slot of the previous step, which the loads issued
         // during this step overwrite.  The first wait after an epilogue drains its stores as well.
@@ -612,8 +625,8 @@ __global__ __launch_bounds__(256, (BX <= 128 ? 2 : 1)) void gemm_dma_kernel(cons
             const int nk = (int)((long)nk_all * (sl + 1) / a.splits) - (int)((long)nk_all * sl / a.splits);
             issue_scales(tw * BW, sl, par);
             for (int kt = 0; kt < nk; ++kt) {
-                if (NSTAGE == 3 && !drain)
-                    __builtin_amdgcn_s_waitcnt(vmcnt_imm(LOADS));
+                if (!drain)
+                    __builtin_amdgcn_s_waitcnt(vmcnt_imm(AHEAD));
                 else
                     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
                 drain = false;
@@ -675,7 +688,7 @@ static int launch_dma_one(const GemmArgs& a, hipStream_t st)
         raised = true;
     }
     const int nitems = tiles * a.splits;
-    constexpr int max_wgs = (BX <= 128) ? 512 : 256;   // resident workgroups: two per compute unit for the small tile
+    constexpr int max_wgs = (smem <= 80 * 1024) ? 512 : 256;   // resident workgroups: two per compute unit when the LDS allows
     hipLaunchKernelGGL(kern, dim3(nitems < max_wgs ? nitems : max_wgs), dim3(256), smem, st, a);
     if (a.splits > 1) {
         const size_t n = (size_t)a.M * a.N;
@@ -690,7 +703,12 @@ static int launch_dma_one(const GemmArgs& a, hipStream_t st)
 template <int XKIND, int WKIND, int ACC>
 static int launch_dma_shape(const GemmArgs& a, hipStream_t st)
 {
-    if (a.tile == TILE_128x160_S2)
+    if constexpr (ACC == FPQ_ACC_FP32) {
+        if (a.tile == TILE_128x160_S4)
+            return a.conv_out ? launch_dma_one<128, 160, 4, XKIND, WKIND, ACC, true>(a, st)
+                              : launch_dma_one<128, 160, 4, XKIND, WKIND, ACC, false>(a, st);
+    }
+    if (a.tile == TILE_128x160_S2 || a.tile == TILE_128x160_S4)   // the four-stage variant exists for FPQ_ACC_FP32 only
         return a.conv_out ? launch_dma_one<128, 160, 2, XKIND, WKIND, ACC, true>(a, st)
                           : launch_dma_one<128, 160, 2, XKIND, WKIND, ACC, false>(a, st);
     return a.conv_out ? launch_dma_one<256, 160, 3, XKIND, WKIND, ACC, true>(a, st)
