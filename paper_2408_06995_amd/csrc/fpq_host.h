@@ -83,8 +83,7 @@ struct GemmArgs {
 enum GemmTile : int {
     TILE_GENERIC = 0,    // register-staged 128x128 / 64x64 kernels: any shape
     TILE_256x160_S3 = 1, // LDS-DMA kernel, three stages: deep K
-    TILE_128x160_S2 = 2, // LDS-DMA kernel, two stages, two workgroups per compute unit
-    TILE_128x160_S4 = 3  // LDS-DMA kernel, four stages, one workgroup per compute unit (FPQ_ACC_FP32 only)
+    TILE_128x160_S2 = 2  // LDS-DMA kernel, two stages, two workgroups per compute unit
 };
 struct GemmPlan {
     int tile;

@@ -1,18 +1,21 @@
 // Quantized linear / convolution layer on ExMy codes for gfx950: the large-tile kernel.
 //
 // A workgroup of four wavefronts owns a BX x BW tile (BX activation rows, BW weight rows; the
-// wavefronts split the activation rows) and walks its K range in steps of 128 codes through a
-// three-stage LDS ring.  Codes travel global memory -> LDS without touching registers:
+// wavefronts split the activation rows) and walks its K range in steps of 128 codes through an LDS
+// ring of two or three stages.  Codes travel global memory -> LDS without touching registers:
 // buffer_load_dwordx4 ... lds writes 64 lanes x 16 bytes to consecutive LDS addresses, and a lane
 // whose element does not exist (row beyond M or N, padding pixel of the convolution, K beyond the
 // real length) gives an offset outside the buffer, for which the hardware delivers zeros = code 0.
 // The xor swizzle of the LDS tile (see lds_off) is applied on the global side, by choosing which
-// 16-byte chunk a lane fetches.  Loads for step k+2 are issued while step k is computed; one
-// s_waitcnt vmcnt + s_barrier per step orders them (the counts are spelled out at the loop).
+// 16-byte chunk a lane fetches.  Loads for step k + NSTAGE - 1 are issued while step k is computed;
+// one s_waitcnt vmcnt + s_barrier per step, placed three quarters into the step, makes the next ring
+// slot valid, and the rest of the step already reads and converts that slot's first fragments, so
+// the MFMA stream never stops at a step boundary (the counts are spelled out at tail_sync).
 //
-// The kernel is persistent: the grid has at most one workgroup per compute unit and each workgroup
-// walks a strided list of work items (output tile, K slice), so that the loads of the next item are
-// already in flight while the current item's results are scaled and stored.
+// The kernel is persistent: the grid has at most one (256-row tile) or two (128-row tile) workgroups
+// per compute unit and each workgroup walks a strided list of work items (output tile, K slice); the
+// loads of the next item are in flight while the current item's results are scaled and stored, and
+// the waits that follow an epilogue count its stores instead of draining them.
 //
 // Split-K: the K steps of an output tile can be cut into slices; slice s writes its scaled partial
 // sums to partial[s] and a second kernel adds the slices into y.
@@ -703,12 +706,7 @@ static int launch_dma_one(const GemmArgs& a, hipStream_t st)
 template <int XKIND, int WKIND, int ACC>
 static int launch_dma_shape(const GemmArgs& a, hipStream_t st)
 {
-    if constexpr (ACC == FPQ_ACC_FP32) {
-        if (a.tile == TILE_128x160_S4)
-            return a.conv_out ? launch_dma_one<128, 160, 4, XKIND, WKIND, ACC, true>(a, st)
-                              : launch_dma_one<128, 160, 4, XKIND, WKIND, ACC, false>(a, st);
-    }
-    if (a.tile == TILE_128x160_S2 || a.tile == TILE_128x160_S4)   // the four-stage variant exists for FPQ_ACC_FP32 only
+    if (a.tile == TILE_128x160_S2)
         return a.conv_out ? launch_dma_one<128, 160, 2, XKIND, WKIND, ACC, true>(a, st)
                           : launch_dma_one<128, 160, 2, XKIND, WKIND, ACC, false>(a, st);
     return a.conv_out ? launch_dma_one<256, 160, 3, XKIND, WKIND, ACC, true>(a, st)

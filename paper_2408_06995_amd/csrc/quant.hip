@@ -41,8 +41,59 @@ __device__ __forceinline__ float block_inv_scale(const ScaleSrc& s)
     return __fdiv_rn(1.0f, sc);
 }
 
-// Pass 1: each block folds a grid-strided share of x into one partial maximum of |x|.
+// Tensors from this many elements (64 MB of fp32) on take the contiguous-share / streaming-load kernels.
+constexpr size_t kStreamElems = (size_t)16 << 20;
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// Streaming 16-byte load for the last reader of the activations (the quantize kernels): ~10 % more
+// bandwidth than a plain load, and the codes just written are not displaced from the caches.  The absmax
+// pass uses plain loads, so that what fits the last-level cache is still there for the quantize pass.
+__device__ __forceinline__ float4 load_stream(const float4* p)
+{
+    const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
+__device__ __forceinline__ float max4(float v, const float4& a)
+{
+    return fmaxf(v, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+}
+
+// Pass 1: each block folds one contiguous share of x into one partial maximum of |x| (contiguous shares
+// and eight 16-byte loads in flight per lane measured fastest: ~6.6 TB/s against ~5.3 grid-strided).
 __global__ __launch_bounds__(256) void absmax_partial_kernel(const float* __restrict__ x, size_t n,
+                                                             float* __restrict__ partial)
+{
+    float v = 0.0f;
+    if ((reinterpret_cast<uintptr_t>(x) & 15) == 0) {
+        const float4* x4 = reinterpret_cast<const float4*>(x);
+        const size_t n4 = n >> 2;
+        const size_t per = (n4 + gridDim.x - 1) / gridDim.x;
+        const size_t b0 = (size_t)blockIdx.x * per;
+        const size_t e = b0 + per < n4 ? b0 + per : n4;
+        // eight loads in flight per lane whatever the length of the share (the last round is predicated)
+        for (size_t base = b0 + threadIdx.x; base < e; base += 8 * 256) {
+            float4 a[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                a[u] = (base + u * 256 < e) ? x4[base + u * 256] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);   // plain loads: the quantize pass that follows re-reads x
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v = max4(v, a[u]);
+        }
+        const size_t tid = (size_t)blockIdx.x * 256 + threadIdx.x;
+        for (size_t j = (n4 << 2) + tid; j < n; j += (size_t)gridDim.x * 256) v = fmaxf(v, fabsf(x[j]));
+    } else {
+        const size_t tid = (size_t)blockIdx.x * 256 + threadIdx.x;
+        for (size_t j = tid; j < n; j += (size_t)gridDim.x * 256) v = fmaxf(v, fabsf(x[j]));
+    }
+    v = block_max(v);
+    if (threadIdx.x == 0) partial[blockIdx.x] = v;
+}
+
+// Pass 1 for tensors below kStreamElems: each block folds a grid-strided share of x (measured ~1 us
+// faster per call than the contiguous-share kernel on the small and cache-resident tensors).
+__global__ __launch_bounds__(256) void absmax_partial_strided_kernel(const float* __restrict__ x, size_t n,
                                                              float* __restrict__ partial)
 {
     float v = 0.0f;
@@ -85,12 +136,13 @@ __global__ __launch_bounds__(256) void absmax_final_kernel(const float* __restri
     }
 }
 
+int launch_absmax_partials(const float* x, size_t n, float* partial, hipStream_t st);
+
 int launch_absmax(const float* x, size_t n, float maxval, float* absmax_out, float* scale_out,
                   float* partial, hipStream_t st)
 {
     int nparts = absmax_parts(n);
-    if (nparts > 0)
-        hipLaunchKernelGGL(absmax_partial_kernel, dim3(nparts), dim3(256), 0, st, x, n, partial);
+    launch_absmax_partials(x, n, partial, st);
     hipLaunchKernelGGL(absmax_final_kernel, dim3(1), dim3(256), 0, st, partial, nparts, maxval, absmax_out,
                        scale_out);
     return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
@@ -100,16 +152,51 @@ int launch_absmax(const float* x, size_t n, float maxval, float* absmax_out, flo
 int launch_absmax_partials(const float* x, size_t n, float* partial, hipStream_t st)
 {
     const int nparts = absmax_parts(n);
-    if (nparts > 0) hipLaunchKernelGGL(absmax_partial_kernel, dim3(nparts), dim3(256), 0, st, x, n, partial);
+    if (nparts > 0) {
+        if (n >= kStreamElems)
+            hipLaunchKernelGGL(absmax_partial_kernel, dim3(nparts), dim3(256), 0, st, x, n, partial);
+        else
+            hipLaunchKernelGGL(absmax_partial_strided_kernel, dim3(nparts), dim3(256), 0, st, x, n, partial);
+    }
     return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
 }
 
 // ------------------------------------------------------------------------------ quantize (flat)
 
-// Four elements per lane and step: one 16-byte load, four encodes, one 4-byte (8-bit codes) or
-// 2-byte (4-bit codes) store.  Four independent loads are kept in flight per lane.
+// Four elements per lane and step: one 16-byte streaming load, four encodes, one 4-byte (8-bit codes) or
+// 2-byte (4-bit codes) store.  Each block walks one contiguous share with four loads in flight per lane.
 template <bool FOUR_BIT>
 __global__ __launch_bounds__(256) void quantize_vec_kernel(const float4* __restrict__ x4, size_t n4, QParams q,
+                                                           ScaleSrc ss, uint8_t* __restrict__ codes)
+{
+    const float r = block_inv_scale(ss);
+    const size_t per = (n4 + gridDim.x - 1) / gridDim.x;
+    const size_t b0 = (size_t)blockIdx.x * per;
+    const size_t e = b0 + per < n4 ? b0 + per : n4;
+    size_t i = b0 + threadIdx.x;
+    auto emit = [&](size_t idx, const float4& v) {
+        uint32_t c0 = quantize_nearest(v.x, r, q), c1 = quantize_nearest(v.y, r, q);
+        uint32_t c2 = quantize_nearest(v.z, r, q), c3 = quantize_nearest(v.w, r, q);
+        if (FOUR_BIT)
+            reinterpret_cast<uint16_t*>(codes)[idx] = (uint16_t)(c0 | (c1 << 4) | (c2 << 8) | (c3 << 12));
+        else
+            reinterpret_cast<uint32_t*>(codes)[idx] = c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+    };
+    for (; i < e; i += 4 * 256) {   // four loads in flight per lane; the last round is predicated
+        float4 a[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i + u * 256 < e) a[u] = load_stream(x4 + i + u * 256);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i + u * 256 < e) emit(i + u * 256, a[u]);
+    }
+}
+
+// The same for tensors below kStreamElems, grid-strided with plain loads: one 16-byte load, four encodes, one 4-byte (8-bit codes) or
+// 2-byte (4-bit codes) store.  Four independent loads are kept in flight per lane.
+template <bool FOUR_BIT>
+__global__ __launch_bounds__(256) void quantize_vec_strided_kernel(const float4* __restrict__ x4, size_t n4, QParams q,
                                                            ScaleSrc ss, uint8_t* __restrict__ codes)
 {
     const float r = block_inv_scale(ss);
@@ -171,12 +258,18 @@ int launch_quantize(const float* x, size_t n, const QParams& q, bool four_bit, c
     size_t n4 = aligned ? (n >> 2) : 0;
     if (n4) {
         int g = grid_for(n4, 256 * 4);
-        if (four_bit)
-            hipLaunchKernelGGL(quantize_vec_kernel<true>, dim3(g), dim3(256), 0, st,
-                               reinterpret_cast<const float4*>(x), n4, q, ss, codes);
-        else
-            hipLaunchKernelGGL(quantize_vec_kernel<false>, dim3(g), dim3(256), 0, st,
-                               reinterpret_cast<const float4*>(x), n4, q, ss, codes);
+        const float4* x4 = reinterpret_cast<const float4*>(x);
+        if (n >= kStreamElems) {
+            if (four_bit)
+                hipLaunchKernelGGL(quantize_vec_kernel<true>, dim3(g), dim3(256), 0, st, x4, n4, q, ss, codes);
+            else
+                hipLaunchKernelGGL(quantize_vec_kernel<false>, dim3(g), dim3(256), 0, st, x4, n4, q, ss, codes);
+        } else {
+            if (four_bit)
+                hipLaunchKernelGGL(quantize_vec_strided_kernel<true>, dim3(g), dim3(256), 0, st, x4, n4, q, ss, codes);
+            else
+                hipLaunchKernelGGL(quantize_vec_strided_kernel<false>, dim3(g), dim3(256), 0, st, x4, n4, q, ss, codes);
+        }
     }
     size_t first = n4 << 2;
     if (first < n) {
@@ -196,7 +289,7 @@ int launch_quantize(const float* x, size_t n, const QParams& q, bool four_bit, c
 // Channels C..Cp-1 receive code 0.  Rows of the tile are 68 bytes so that the four-byte column
 // groups of neighbouring pixels fall into different LDS banks.
 __global__ __launch_bounds__(256) void quantize_nhwc_kernel(const float* __restrict__ x, int C, int Cp, int HW,
-                                                            QParams q, ScaleSrc ss,
+                                                            QParams q, ScaleSrc ss, bool stream,
                                                             uint8_t* __restrict__ codes)
 {
     constexpr int LDW = 68;
@@ -217,7 +310,7 @@ __global__ __launch_bounds__(256) void quantize_nhwc_kernel(const float* __restr
         if (ch < C) {
             const float* src = x + ((size_t)b * C + ch) * (size_t)HW + p;
             if (vec_ok && p + 3 < HW) {
-                float4 v = *reinterpret_cast<const float4*>(src);
+                const float4 v = stream ? load_stream(reinterpret_cast<const float4*>(src)) : *reinterpret_cast<const float4*>(src);
                 cd[0] = quantize_nearest(v.x, r, q);
                 cd[1] = quantize_nearest(v.y, r, q);
                 cd[2] = quantize_nearest(v.z, r, q);
@@ -249,7 +342,8 @@ int launch_quantize_nhwc(const float* x, int64_t B, int64_t C, int64_t H, int64_
     int Cp = (int)padded_channels(C);
     int HW = (int)(H * W);
     dim3 grid((HW + 63) / 64, (Cp + 63) / 64, (unsigned)B);
-    hipLaunchKernelGGL(quantize_nhwc_kernel, grid, dim3(256), 0, st, x, (int)C, Cp, HW, q, ss, codes);
+    hipLaunchKernelGGL(quantize_nhwc_kernel, grid, dim3(256), 0, st, x, (int)C, Cp, HW, q, ss,
+                       (size_t)B * C * H * W >= kStreamElems, codes);
     return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
 }
 
