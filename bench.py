@@ -28,6 +28,10 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_FP8_TFLOPS = 5000.0    # MI355X dense fp8 MFMA (also the rate of fp8 x fp4)
 PEAK_HBM_GBS = 8000.0
+# HBM-side bytes per layer launch from the two hardware-counter passes whose summary is
+# profiles/cfg5_step_hbm_traffic_pmc.txt (25.77 MB fetched + 34.70 MB written); a profiler figure, not
+# measurable from inside this script, hence only for the workload and mode it was taken on.
+MEASURED_TRAFFIC = {("cfg5", "fp32"): 60.47e6}
 
 
 def parse():
@@ -222,10 +226,21 @@ def main():
         return tot_ms, tot_fl, nlaunch, {}
 
     g_ms, g_fl, g_n, per_layer = gemm_breakdown(acc)
+    # algorithmic bytes of those launches: activation codes once (not the im2col expansion), packed weights, fp32 output
+    alg_bytes = 0
+    for s in states:
+        L = s.L
+        if codes_bufs[L.name] is None:
+            continue
+        alg_bytes += 2 * (codes_bufs[L.name].numel() + 4 * L.M * L.N) + s.packed["w8"].numel() + s.packed["w4"].numel()
     peak = PEAK_BF16_TFLOPS if acc == B.FPQ_ACC_FP32 else PEAK_FP8_TFLOPS
     achieved = g_fl / (g_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "fpq::gemm_dma_kernel / gemm_kernel (all GEMM and conv launches of one step, one graph)", "achieved": round(achieved, 2),
-                "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
+                "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                "traffic": MEASURED_TRAFFIC.get((args.workload, args.acc)),
+                "traffic_unit": "bytes per launch (L2 <-> fabric, rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, "
+                                "factors from a 256 MiB copy kernel)",
+                "algorithmic_bytes_per_launch": round(alg_bytes / g_n),
                 "launches": g_n, "avg_launch_us": round(g_ms * 1e3 / g_n, 2),
                 "gemm_ms_per_step": round(g_ms, 4)}
 
@@ -251,6 +266,44 @@ def main():
                                  "value": round(flops_step / sec_o / 1e12, 3), "unit": "TFLOP/s",
                                  "gemm_achieved": round(o_fl / (o_ms * 1e-3) / 1e12, 2), "peak": peak_o,
                                  "frac": round(o_fl / (o_ms * 1e-3) / 1e12 / peak_o, 4)}
+        # the single-layer configurations, layer kernel alone on prepared codes (16 launches in one graph)
+        singles = {}
+        for cname, cidx in (("cfg2", 2), ("cfg4", 4)):
+            L = synth.config_layers(cidx)[0]
+            xs = synth.activations_torch((L.B, L.Cin, L.H, L.W), 1, dev)
+            w = synth.weights_torch((L.Cout, L.Cin, L.k, L.k), 2, dev)
+            st2 = torch.empty(2, dtype=torch.float32, device=dev)
+            B.fpq_absmax(xs, FX[3], st2[0:1], st2[1:2], amax_ws)
+            cb = torch.empty(L.B * L.H * L.W * B.fpq_padded_channels(L.Cin), dtype=torch.uint8, device=dev)
+            B.fpq_quantize_nhwc(xs, FX, 0.0, st2[1:2], cb)
+            yb = torch.empty(L.M * L.N, dtype=torch.float32, device=dev)
+            wsb = torch.empty(max(256, B.fpq_conv2d_workspace_size(L.B, L.Cin, L.H, L.W, L.Cout, L.k, L.k, L.stride, L.pad, 0)),
+                              dtype=torch.uint8, device=dev)
+            for tag, fw in (("w8a8", FW8), ("w4a8", FW4)):
+                pk = torch.empty(B.fpq_packed_size(L.N, L.Cin, L.k, L.k, fw), dtype=torch.uint8, device=dev)
+                sw = torch.empty(L.N, dtype=torch.float32, device=dev)
+                B.fpq_pack_weights(w, fw, None, None, pk, sw, None)
+
+                def one():
+                    B.fpq_conv2d(cb, 0, FX, 0.0, st2[1:2], pk, fw, sw, None, yb, L.B, L.Cin, L.H, L.W, L.Cout, L.k, L.k,
+                                 L.stride, L.pad, acc, wsb)
+                one()
+                torch.cuda.synchronize()
+                g1 = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g1):
+                    for _ in range(16):
+                        one()
+                g1.replay()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(4):
+                    g1.replay()
+                e1.record()
+                e1.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / 64
+                singles["%s_%s" % (cname, tag)] = {"us_per_layer": round(us, 2),
+                                                   "TFLOP/s": round(synth.flops(L) / us / 1e6, 1)}
+        out["single_layer_configs"] = singles
         # activation-quantize bandwidth: 64 Mi elements per launch, rotating over 8 buffers (2.7 GB) so that the
         # last-level cache cannot serve the reads; algorithmic bytes = 5 per element (4 read + 1 written)
         n = 64 << 20
@@ -280,10 +333,10 @@ def main():
 
     if not args.no_cpu_baseline:
         import oracle
-        # bounded sample of the same kind of work: the config-2 conv layer (7.55 GFLOP) and a 1/4 row sample of
-        # the config-4 conv (15.1 GFLOP), W8A8, through the oracle as it stands, on the host cores
+        # bounded sample of the same kind of work (~128 GFLOP), W8A8, through the oracle as it stands, on the host cores
         t_cpu, fl_cpu = 0.0, 0.0
-        for (shape, wshape, npix) in (((1, 320, 64, 64), (320, 320, 3, 3), None), ((8, 1280, 16, 16), (1280, 1280, 3, 3), 512)):
+        for (shape, wshape, npix) in (((1, 320, 64, 64), (320, 320, 3, 3), None), ((8, 1280, 16, 16), (1280, 1280, 3, 3), None),
+                                      ((8, 640, 32, 32), (640, 640, 3, 3), None)):
             x = synth.activations(shape, 2000)
             w = synth.weights(wshape, 2500)
             t0 = time.perf_counter()
@@ -297,8 +350,9 @@ def main():
             fl_cpu += 2.0 * (M if pix is None else len(pix)) * wshape[0] * wshape[1] * 9
         out["cpu_baseline"] = {"value": round(fl_cpu / t_cpu / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
                                "kind": "oracle",
-                               "sample": "oracle quantize + pack + conv2d: config-2 conv in full and 512 of 2048 output "
-                                         "pixels of the config-4 conv (%.1f GFLOP, %.1f s)" % (fl_cpu / 1e9, t_cpu)}
+                               "sample": "oracle absmax + quantize + pack + conv2d, W8A8: the config-2 and config-4 convs in "
+                                         "full and a 640-channel 32x32 conv of config 5 "
+                                         "(%.1f GFLOP, %.1f s)" % (fl_cpu / 1e9, t_cpu)}
     print(json.dumps(out))
 
 
