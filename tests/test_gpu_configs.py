@@ -31,18 +31,20 @@ def run_layer_gpu(L, x_t, w_t, h_t, fx, fw, acc, bias_t=None):
     sw = torch.empty(L.N, dtype=torch.float32, device=DEV)
     wcodes = torch.empty(L.N * L.K, dtype=torch.uint8, device=DEV)
     B.fpq_pack_weights(w_t.reshape(wshape), fw, None, h_t, packed, sw, wcodes)
-    sc = torch.empty(2, dtype=torch.float32, device=DEV)
-    aws = torch.zeros(1026, dtype=torch.float32, device=DEV)
-    B.fpq_absmax(x_t, fx[3], sc[0:1], sc[1:2], aws)
     y = torch.full((L.M * L.N,), float("nan"), dtype=torch.float32, device=DEV)
+    # dynamic-scale mode (what bench.py calls): absmax, scale, quantize and the layer in one call
     if L.kind == "conv":
-        ws = torch.empty(B.fpq_conv2d_workspace_size(L.B, L.Cin, L.H, L.W, L.Cout, L.k, L.k, L.stride, L.pad, 1),
+        ws = torch.empty(B.fpq_conv2d_workspace_size(L.B, L.Cin, L.H, L.W, L.Cout, L.k, L.k, L.stride, L.pad, 2),
                          dtype=torch.uint8, device=DEV)
-        B.fpq_conv2d(x_t, 1, fx, 0.0, sc[1:2], packed, fw, sw, bias_t, y, L.B, L.Cin, L.H, L.W, L.Cout, L.k, L.k,
-                     L.stride, L.pad, acc, ws)
+        B.fpq_conv2d(x_t, B.FPQ_X_FP32_DYNAMIC, fx, 0.0, None, packed, fw, sw, bias_t, y, L.B, L.Cin, L.H, L.W, L.Cout,
+                     L.k, L.k, L.stride, L.pad, acc, ws)
     else:
-        ws = torch.empty(max(256, B.fpq_gemm_workspace_size(L.M, L.N, L.K, 1)), dtype=torch.uint8, device=DEV)
-        B.fpq_gemm(x_t, 1, fx, 0.0, sc[1:2], packed, fw, sw, bias_t, y, L.M, L.N, L.K, acc, ws)
+        ws = torch.empty(B.fpq_gemm_workspace_size(L.M, L.N, L.K, 2), dtype=torch.uint8, device=DEV)
+        B.fpq_gemm(x_t, B.FPQ_X_FP32_DYNAMIC, fx, 0.0, None, packed, fw, sw, bias_t, y, L.M, L.N, L.K, acc, ws)
+    torch.cuda.synchronize()
+    # the workspace ends with 1024 partial maxima and a 256-byte slot holding [scale, absmax]
+    pub = ws[-256:-248].view(torch.float32)
+    sc = torch.stack([pub[1], pub[0]])
     torch.cuda.synchronize()
     return y, sc.cpu().numpy(), ws, wcodes, sw
 
