@@ -266,44 +266,62 @@ def main():
                                  "value": round(flops_step / sec_o / 1e12, 3), "unit": "TFLOP/s",
                                  "gemm_achieved": round(o_fl / (o_ms * 1e-3) / 1e12, 2), "peak": peak_o,
                                  "frac": round(o_fl / (o_ms * 1e-3) / 1e12 / peak_o, 4)}
-        # the single-layer configurations, layer kernel alone on prepared codes (16 launches in one graph)
+        # single layers, layer kernel alone on prepared codes (16 launches in one graph), both accumulate modes:
+        # configurations 2 and 4, and from configuration 5 a deep-K conv and an output-bound linear layer
         singles = {}
-        for cname, cidx in (("cfg2", 2), ("cfg4", 4)):
-            L = synth.config_layers(cidx)[0]
-            xs = synth.activations_torch((L.B, L.Cin, L.H, L.W), 1, dev)
-            w = synth.weights_torch((L.Cout, L.Cin, L.k, L.k), 2, dev)
+        picks = [("cfg2_conv_320_64x64_b1", synth.config_layers(2)[0]), ("cfg4_conv_1280_16x16_b8", synth.config_layers(4)[0]),
+                 ("cfg5_conv_1280_32x32_b8", synth.conv("c", 8, 1280, 32, 32, 1280, 3, 1)),
+                 ("cfg5_linear_32768x320x2560", synth.linear("l", 32768, 320, 2560))]
+        for cname, L in picks:
+            if L.kind == "conv":
+                xs = synth.activations_torch((L.B, L.Cin, L.H, L.W), 1, dev)
+                wshape, kk = (L.Cout, L.Cin, L.k, L.k), L.k
+                cb = torch.empty(L.B * L.H * L.W * B.fpq_padded_channels(L.Cin), dtype=torch.uint8, device=dev)
+                wsz = B.fpq_conv2d_workspace_size(L.B, L.Cin, L.H, L.W, L.Cout, L.k, L.k, L.stride, L.pad, 0)
+            else:
+                xs = synth.activations_torch((L.M, L.K), 1, dev)
+                wshape, kk = (L.N, L.K), 1
+                cb = torch.empty(L.M * L.K, dtype=torch.uint8, device=dev)
+                wsz = B.fpq_gemm_workspace_size(L.M, L.N, L.K, 0)
+            w = synth.weights_torch(wshape, 2, dev)
             st2 = torch.empty(2, dtype=torch.float32, device=dev)
             B.fpq_absmax(xs, FX[3], st2[0:1], st2[1:2], amax_ws)
-            cb = torch.empty(L.B * L.H * L.W * B.fpq_padded_channels(L.Cin), dtype=torch.uint8, device=dev)
-            B.fpq_quantize_nhwc(xs, FX, 0.0, st2[1:2], cb)
+            if L.kind == "conv":
+                B.fpq_quantize_nhwc(xs, FX, 0.0, st2[1:2], cb)
+            else:
+                B.fpq_quantize(xs, FX, 0.0, st2[1:2], cb)
             yb = torch.empty(L.M * L.N, dtype=torch.float32, device=dev)
-            wsb = torch.empty(max(256, B.fpq_conv2d_workspace_size(L.B, L.Cin, L.H, L.W, L.Cout, L.k, L.k, L.stride, L.pad, 0)),
-                              dtype=torch.uint8, device=dev)
+            wsb = torch.empty(max(256, wsz), dtype=torch.uint8, device=dev)
+            entry = {}
             for tag, fw in (("w8a8", FW8), ("w4a8", FW4)):
-                pk = torch.empty(B.fpq_packed_size(L.N, L.Cin, L.k, L.k, fw), dtype=torch.uint8, device=dev)
+                pk = torch.empty(B.fpq_packed_size(L.N, L.Cin, kk, kk, fw), dtype=torch.uint8, device=dev)
                 sw = torch.empty(L.N, dtype=torch.float32, device=dev)
                 B.fpq_pack_weights(w, fw, None, None, pk, sw, None)
-
-                def one():
-                    B.fpq_conv2d(cb, 0, FX, 0.0, st2[1:2], pk, fw, sw, None, yb, L.B, L.Cin, L.H, L.W, L.Cout, L.k, L.k,
-                                 L.stride, L.pad, acc, wsb)
-                one()
-                torch.cuda.synchronize()
-                g1 = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(g1):
-                    for _ in range(16):
-                        one()
-                g1.replay()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                for _ in range(4):
+                for mname, mode in (("fp32", B.FPQ_ACC_FP32), ("fp8mfma", B.FPQ_ACC_FP8_MFMA)):
+                    def one():
+                        if L.kind == "conv":
+                            B.fpq_conv2d(cb, 0, FX, 0.0, st2[1:2], pk, fw, sw, None, yb, L.B, L.Cin, L.H, L.W, L.Cout, L.k,
+                                         L.k, L.stride, L.pad, mode, wsb)
+                        else:
+                            B.fpq_gemm(cb, 0, FX, 0.0, st2[1:2], pk, fw, sw, None, yb, L.M, L.N, L.K, mode, wsb)
+                    one()
+                    torch.cuda.synchronize()
+                    g1 = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g1):
+                        for _ in range(16):
+                            one()
                     g1.replay()
-                e1.record()
-                e1.synchronize()
-                us = e0.elapsed_time(e1) * 1e3 / 64
-                singles["%s_%s" % (cname, tag)] = {"us_per_layer": round(us, 2),
-                                                   "TFLOP/s": round(synth.flops(L) / us / 1e6, 1)}
-        out["single_layer_configs"] = singles
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(4):
+                        g1.replay()
+                    e1.record()
+                    e1.synchronize()
+                    us = e0.elapsed_time(e1) * 1e3 / 64
+                    entry["%s_%s" % (tag, mname)] = {"us": round(us, 2), "TFLOP/s": round(synth.flops(L) / us / 1e6, 1)}
+            singles[cname] = entry
+            del xs, w, cb, yb, wsb
+        out["single_layers"] = singles
         # activation-quantize bandwidth: 64 Mi elements per launch, rotating over 8 buffers (2.7 GB) so that the
         # last-level cache cannot serve the reads; algorithmic bytes = 5 per element (4 read + 1 written)
         n = 64 << 20

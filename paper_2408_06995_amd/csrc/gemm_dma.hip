@@ -371,52 +371,65 @@ __global__ __launch_bounds__(256, ((BX <= 128 && NSTAGE <= 2) ? 2 : 1)) void gem
         static_assert(3 * LOADS <= 6 * NM, "the loads of a step must be issued before its tail_sync");
     };
 
-    // ---- FPQ_ACC_FP8_MFMA: codes feed the 8-bit / 4-bit MFMA directly, two 64-code steps per K step.  The
+    // ---- FPQ_ACC_FP8_MFMA: codes feed the 8-bit / 4-bit MFMA directly, two 64-code MFMA steps per K step.  The
     // instruction pairs byte i < 16 of an 8-bit operand (lane half g) with K index 16g + i and byte 16 + i
     // with 32 + 16g + i, and nibble i of a 4-bit operand with K index 32g + i; the chunk choices follow.
-    auto compute8 = [&](int stage, int to_stage) {
+    // Same pipeline as above with register fragments double-buffered per MFMA step: while the MFMAs of one
+    // 64-code step run, the fragments of the next step are read from LDS (those of the next ring slot after
+    // the tail_sync that opens the second step); the loads of the K step NSTAGE - 1 ahead go out two per slot
+    // during the first step, so all of them precede the tail_sync.
+    v8i frag8[2][NF];
+    auto lds_read8 = [&](int stage, int kk, int f) -> v8i {
         const uint8_t* xs = smem + stage * STAGE;
         const uint8_t* ws = xs + XTILE;
         const uint8_t* ps = P_IS_W ? ws : xs;
         const uint8_t* qs = P_IS_W ? xs : ws;
-#pragma unroll
-        for (int idx = 0; idx < LOADS; ++idx) issue_one(idx, to_stage);
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            v8i pfr[MI], qfr[NI];
-#pragma unroll
-            for (int i = 0; i < MI; ++i) {
-                const int row = prow0 + 32 * i;
-                union { v8i v; uint4 q[2]; } u;
-                if (P4) {
-                    u.q[0] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 2 * kk + g));
-                    u.q[1] = make_uint4(0, 0, 0, 0);
-                } else {
-                    u.q[0] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 4 * kk + g));
-                    u.q[1] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 4 * kk + 2 + g));
-                }
-                pfr[i] = u.v;
+        union { v8i v; uint4 q[2]; } u;
+        if (f < MI) {
+            const int row = prow0 + 32 * f;
+            if (P4) {
+                u.q[0] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 2 * kk + g));
+                u.q[1] = make_uint4(0, 0, 0, 0);
+            } else {
+                u.q[0] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 4 * kk + g));
+                u.q[1] = *reinterpret_cast<const uint4*>(ps + lds_off<PROWB>(row, 4 * kk + 2 + g));
             }
-#pragma unroll
-            for (int i = 0; i < NI; ++i) {
-                const int row = qrow0 + 32 * i;
-                union { v8i v; uint4 q[2]; } u;
-                if (Q4) {
-                    u.q[0] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 2 * kk + g));
-                    u.q[1] = make_uint4(0, 0, 0, 0);
-                } else {
-                    u.q[0] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 4 * kk + g));
-                    u.q[1] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 4 * kk + 2 + g));
-                }
-                qfr[i] = u.v;
+        } else {
+            const int row = qrow0 + 32 * (f - MI);
+            if (Q4) {
+                u.q[0] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 2 * kk + g));
+                u.q[1] = make_uint4(0, 0, 0, 0);
+            } else {
+                u.q[0] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 4 * kk + g));
+                u.q[1] = *reinterpret_cast<const uint4*>(qs + lds_off<QROWB>(row, 4 * kk + 2 + g));
             }
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int jj = 0; jj < NI; ++jj)
-                    acc[i][jj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pfr[i], qfr[jj], acc[i][jj], PFMT, QFMT,
-                                                                               0, 0, 0, 0);
         }
+        return u.v;
+    };
+    auto first_fragments8 = [&](int stage) {
+#pragma unroll
+        for (int f = 0; f < NF; ++f) frag8[0][f] = lds_read8(stage, 0, f);
+    };
+    auto compute8 = [&](int stage, int next_stage, int to_stage, int mode) {
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+#pragma unroll
+            for (int k = 0; k < NM; ++k) {
+                const int i = k / NI, jj = k - i * NI;
+                acc[i][jj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag8[st][i], frag8[st][MI + jj], acc[i][jj],
+                                                                           PFMT, QFMT, 0, 0, 0, 0);
+                if (st == 1 && k == 0) tail_sync(mode);
+#pragma unroll
+                for (int f = k; f < NF; f += NM)
+                    frag8[st ^ 1][f] = st == 0 ? lds_read8(stage, 1, f) : lds_read8(next_stage, 0, f);
+                if (st == 0) {
+                    if (2 * k < LOADS) issue_one(2 * k, to_stage);
+                    if (2 * k + 1 < LOADS) issue_one(2 * k + 1, to_stage);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        static_assert(LOADS <= 2 * NM, "the loads of a step must be issued before its tail_sync");
     };
 
     // ---- epilogue of one work item: acc * (sx * alpha * sw[n]) + bias[n].
@@ -586,13 +599,16 @@ __global__ __launch_bounds__(256, ((BX <= 128 && NSTAGE <= 2) ? 2 : 1)) void gem
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
     };
-    if constexpr (ACC == FPQ_ACC_FP32) {
+    {
         // the first ring slot: its group is the oldest of the NSTAGE - 1 outstanding ones
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(LOADS * (NSTAGE - 2)));
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        first_fragments(0);
+        if constexpr (ACC == FPQ_ACC_FP32)
+            first_fragments(0);
+        else
+            first_fragments8(0);
         int after = W_FIRST;   // what precedes the current item: nothing, counted stores, or uncounted stores
         int since = 0;         // K steps since then
         for (int c_item = q; c_item < nitems; c_item += G) {
@@ -602,7 +618,11 @@ __global__ __launch_bounds__(256, ((BX <= 128 && NSTAGE <= 2) ? 2 : 1)) void gem
             issue_scales(tw * BW, sl, par);
             for (int kt = 0; kt < nk; ++kt) {
                 const int nstage = (cstage + 1 == NSTAGE) ? 0 : cstage + 1;
-                compute(cstage, nstage, istage, since < NSTAGE - 2 ? after : (int)W_NORMAL);
+                const int mode = since < NSTAGE - 2 ? after : (int)W_NORMAL;
+                if constexpr (ACC == FPQ_ACC_FP32)
+                    compute(cstage, nstage, istage, mode);
+                else
+                    compute8(cstage, nstage, istage, mode);
                 ++since;
                 issued();
                 cstage = nstage;
@@ -613,38 +633,6 @@ __global__ __launch_bounds__(256, ((BX <= 128 && NSTAGE <= 2) ? 2 : 1)) void gem
             after = epilogue(tx * BX, tw * BW, sl, par) ? W_AFTER_STORES : W_DRAIN;
             since = 0;
             par ^= 1;
-            clear_acc();
-        }
-    } else {
-        // On entry to a step the wave's outstanding loads are the NSTAGE - 1 groups issued last, so
-        // vmcnt <= AHEAD = LOADS * (NSTAGE - 2) means the oldest of them, this step's, has landed (the two scale
-        // loads of an item only make the wait stricter); the barrier then says the same of every wave, and
-        // that every wave has finished reading the ring slot of the previous step, which the loads issued
-        // during this step overwrite.  The first wait after an epilogue drains its stores as well.
-        bool drain = false;
-        for (int c_item = q; c_item < nitems; c_item += G) {
-            const int tile = c_item / a.splits, sl = c_item - tile * a.splits;
-            const int tx = tile / tiles_w, tw = tile - tx * tiles_w;
-            const int nk = (int)((long)nk_all * (sl + 1) / a.splits) - (int)((long)nk_all * sl / a.splits);
-            issue_scales(tw * BW, sl, par);
-            for (int kt = 0; kt < nk; ++kt) {
-                if (!drain)
-                    __builtin_amdgcn_s_waitcnt(vmcnt_imm(AHEAD));
-                else
-                    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-                drain = false;
-                asm volatile("" ::: "memory");
-                __builtin_amdgcn_s_barrier();
-                asm volatile("" ::: "memory");
-                compute8(cstage, istage);   // the loads of the step NSTAGE - 1 ahead are issued first
-                issued();
-                cstage = (cstage + 1 == NSTAGE) ? 0 : cstage + 1;
-            }
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(LOADS));
-            asm volatile("" ::: "memory");
-            epilogue(tx * BX, tw * BW, sl, par);
-            par ^= 1;
-            drain = true;
             clear_acc();
         }
     }
