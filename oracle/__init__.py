@@ -60,6 +60,15 @@ def lib():
                                     + [C.c_long] * 9 + [C.c_void_p, C.c_long, C.c_void_p, C.c_void_p])
         L.oracle_num_threads.restype = C.c_int
         L.oracle_num_threads.argtypes = []
+        L.oracle_search_candidate.restype = C.c_float
+        L.oracle_search_candidate.argtypes = [C.c_float, C.c_int, C.c_int]
+        L.oracle_search_scale.restype = C.c_float
+        L.oracle_search_scale.argtypes = [C.c_int, C.c_int, C.c_float]
+        L.oracle_candidate_mse.restype = C.c_double
+        L.oracle_candidate_mse.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_float]
+        L.oracle_search.restype = None
+        L.oracle_search.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p,
+                                    C.c_void_p]
         _lib = L
     return _lib
 
@@ -201,6 +210,33 @@ def conv2d(xq, fx, sx, wq, fw, sw, bias=None, stride=1, pad=0, pix=None):
                         B, Cin, H, W, Cout, kh, kw, stride, pad,
                         _p(pix_), 0 if pix_ is None else pix_.size, _p(Y), _p(T))
     return Y, T
+
+
+def search_candidate(absmax, j, J):
+    """Section V-A: max-value candidate j of J, evenly spaced in (0, absmax]."""
+    return float(lib().oracle_search_candidate(float(absmax), int(j), int(J)))
+
+
+def search_scale(e, m, cj):
+    """Scale that, with the integer bias 2^(e-1), realises encoding (e, m) with max value cj."""
+    return float(lib().oracle_search_scale(int(e), int(m), float(cj)))
+
+
+def candidate_mse(x, e, m, cj):
+    x = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
+    return float(lib().oracle_candidate_mse(_p(x), x.size, int(e), int(m), float(cj)))
+
+
+def search(x, encodings, J=111):
+    """Algorithm 1 (Section V-A) over encodings [(e, m), ...] x J bias candidates.
+    Returns (mse[n_enc, J] float64, (best encoding index, best bias index))."""
+    x = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
+    ee = np.ascontiguousarray([e for e, _ in encodings], dtype=np.int32)
+    mm = np.ascontiguousarray([m for _, m in encodings], dtype=np.int32)
+    mse = np.empty(len(encodings) * J, dtype=np.float64)
+    best = np.zeros(2, dtype=np.int32)
+    lib().oracle_search(_p(x), x.size, _p(ee), _p(mm), len(encodings), int(J), _p(mse), _p(best))
+    return mse.reshape(len(encodings), J), (int(best[0]), int(best[1]))
 
 
 def num_threads():

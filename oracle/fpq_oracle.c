@@ -30,7 +30,16 @@
  *     clipped full-precision weight (as in AdaRound, which the section adapts), the floor
  *     is towards minus infinity, and s_i is taken from the clipped, unrounded weight;
  *   - a value that rounds to zero keeps the sign bit of the input;
- *   - NaN inputs are outside the contract (result unspecified).
+ *   - NaN inputs are outside the contract (result unspecified);
+ *   - Algorithm 1 (Section V-A) starts from prev_mse = 0 and keeps a candidate only when
+ *     prev_mse > curr_mse, which as printed never accepts anything: read as prev_mse =
+ *     +infinity (first strict minimum in scan order, encodings outer, biases inner);
+ *   - its bias candidates are "evenly spaced values between the minimum and maximum of the
+ *     data", turned into biases by Eq. (7): read on magnitudes (the grid is symmetric) as
+ *     the max values c_j = absmax * (j + 1) / J, j = 0 .. J-1; the real-valued bias of c_j
+ *     is carried as the integer bias b0 = 2^(e-1) plus the scale c_j / c0, c0 = Eq. (7) at
+ *     b0 (the grid of a real bias is a scaled copy of the grid of an integer one);
+ *   - the error of a candidate is the mean over the tensor of (x - dequantized x)^2.
  *
  * Codes are held one per byte everywhere in this file (also for 4-bit formats);
  * oracle_pack4 produces the two-per-byte boundary form (even index in the low nibble).
@@ -287,6 +296,63 @@ void oracle_conv2d(const uint8_t *xq, int ex, int mx, int bx, float sx,
             T[o] = sc * accabs;
         }
     }
+}
+
+/* ----------------------------- Section V-A, Algorithm 1: encoding and bias search */
+
+/* Max-value candidate j of J for a tensor whose largest magnitude is absmax (1 if the
+ * tensor is all zero): evenly spaced in (0, absmax], the last one equal to absmax. */
+float oracle_search_candidate(float absmax, int j, int J)
+{
+    double a = absmax > 0.0f ? (double)absmax : 1.0;
+    return (float)(a * (double)(j + 1) / (double)J);
+}
+
+/* Integer bias + scale form of "encoding (e, m) with max value cj": b0 = 2^(e-1),
+ * scale = fl32(cj / c0) with c0 = Eq. (7) at b0. */
+float oracle_search_scale(int e, int m, float cj)
+{
+    int b0 = 1 << (e - 1);
+    return (float)((double)cj / oracle_format_max(e, m, b0));
+}
+
+/* Mean squared error between x and its quantized-dequantized copy for one candidate. */
+double oracle_candidate_mse(const float *x, size_t n, int e, int m, float cj)
+{
+    int b0 = 1 << (e - 1);
+    double c0 = oracle_format_max(e, m, b0);
+    float scale = oracle_search_scale(e, m, cj);
+    double sum = 0.0;
+    for (size_t i = 0; i < n; ++i) {
+        unsigned code = oracle_quantize_one(x[i], e, m, b0, c0, scale);
+        double q = oracle_decode(e, m, b0, code) * (double)scale;
+        double d = (double)x[i] - q;
+        sum += d * d;
+    }
+    return n ? sum / (double)n : 0.0;
+}
+
+/* Algorithm 1 over n_enc encodings x J bias candidates.  mse[i * J + j] receives every
+ * candidate's error; best[0], best[1] the chosen encoding and bias index. */
+void oracle_search(const float *x, size_t n, const int *enc_e, const int *enc_m, int n_enc, int J,
+                   double *mse, int *best)
+{
+    float absmax = oracle_absmax(x, n);
+    int total = n_enc * J;
+#pragma omp parallel for schedule(dynamic)
+    for (int cnd = 0; cnd < total; ++cnd) {
+        int i = cnd / J, j = cnd % J;
+        mse[cnd] = oracle_candidate_mse(x, n, enc_e[i], enc_m[i], oracle_search_candidate(absmax, j, J));
+    }
+    double prev_mse = INFINITY;
+    best[0] = best[1] = 0;
+    for (int i = 0; i < n_enc; ++i)
+        for (int j = 0; j < J; ++j)
+            if (prev_mse > mse[i * J + j]) {
+                best[0] = i;
+                best[1] = j;
+                prev_mse = mse[i * J + j];
+            }
 }
 
 int oracle_num_threads(void)

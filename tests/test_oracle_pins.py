@@ -472,3 +472,74 @@ def test_absmax_and_scale():
     assert oracle.absmax(x) == float(np.abs(x).max())
     assert oracle.scale_from_absmax(10.0, 448.0) == float(np.float32(10.0) / np.float32(448.0))
     assert oracle.scale_from_absmax(0.0, 448.0) == 1.0
+
+
+# ------------------------------------------------------------------------------ Algorithm 1 (Section V-A)
+
+FP8_ENCODINGS = [(2, 5), (3, 4), (4, 3), (5, 2)]
+FP4_ENCODINGS = [(1, 2), (2, 1)]
+
+
+def real_bias_grid(e, m, c):
+    """Every magnitude of the (e, m) grid whose real-valued bias makes Eq. (7) equal c, by Eq. (5) in float64."""
+    b = (2 ** e - 1) - math.log2(c / (2.0 - 2.0 ** -m))          # Eq. (7) solved for the bias
+    vals = [f / 2 ** m * 2.0 ** (1 - b) for f in range(2 ** m)]  # p = 0 row
+    vals += [(1 + f / 2 ** m) * 2.0 ** (p - b) for p in range(1, 2 ** e) for f in range(2 ** m)]
+    return np.array(sorted(vals))
+
+
+@pytest.mark.parametrize("encodings", [FP8_ENCODINGS, FP4_ENCODINGS])
+def test_search_mse_equals_brute_force_on_real_bias_grids(encodings):
+    """Each candidate's error against a nearest-value search over the grid enumerated from Eq. (5) with the
+    real-valued bias that Eq. (7) gives for its max value: checks the candidate spacing, the integer-bias +
+    scale representation and the error definition without calling the oracle's quantizer."""
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal(257) * np.where(rng.random(257) < 0.02, 20.0, 1.0)).astype(np.float32)
+    J = 23
+    mse, best = oracle.search(x, encodings, J)
+    absmax = np.abs(x).max()
+    want = np.empty_like(mse)
+    for i, (e, m) in enumerate(encodings):
+        for j in range(J):
+            c = float(np.float32(np.float64(absmax) * (j + 1) / J))
+            g = real_bias_grid(e, m, c)
+            assert abs(g[-1] - c) <= 1e-12 * c
+            a = np.minimum(np.abs(x.astype(np.float64)), c)
+            q = g[np.abs(a[:, None] - g[None, :]).argmin(axis=1)]
+            want[i, j] = np.mean((np.abs(x.astype(np.float64)) - q) ** 2)
+    assert np.allclose(mse, want, rtol=1e-5, atol=0)
+    flat = want.reshape(-1)
+    assert mse[best] <= flat.min() * (1 + 1e-5)
+
+
+def test_search_finds_the_grid_the_data_lies_on():
+    s = 0.37
+    vals = np.array([0, .5, 1, 1.5, 2, 3, 4, 6]) * s
+    rng = np.random.default_rng(1)
+    x = (rng.choice(vals, 500) * rng.choice([-1.0, 1.0], 500)).astype(np.float32)
+    x[0] = 6 * s
+    mse, best = oracle.search(x, FP4_ENCODINGS, 111)
+    assert best == (1, 110) and mse[1, 110] == 0.0          # E2M1 with max value = absmax reproduces x
+    assert (mse[0] > 0).all()                                # a uniform E1M2 grid cannot
+    assert (mse.reshape(-1)[:best[0] * 111 + best[1]] > 0).all()
+
+
+def test_search_scan_order_and_scaling():
+    mse, best = oracle.search(np.zeros(64, np.float32), FP8_ENCODINGS, 111)
+    assert best == (0, 0) and (mse == 0).all()               # first candidate wins ties (strict comparison)
+    x = synth.activations((4096,), 77)
+    m1, b1 = oracle.search(x, FP8_ENCODINGS, 37)
+    m2, b2 = oracle.search(x * np.float32(4.0), FP8_ENCODINGS, 37)
+    assert b1 == b2 and np.array_equal(m2, m1 * 16.0)        # powers of two commute with every step
+
+
+def test_search_prefers_mantissa_for_uniform_and_exponent_for_wide_range_data():
+    rng = np.random.default_rng(2)
+    uni = rng.uniform(-1, 1, 20000).astype(np.float32)
+    _, best_u = oracle.search(uni, FP8_ENCODINGS, 111)
+    assert FP8_ENCODINGS[best_u[0]] == (2, 5)
+    # unit normal data with 1 % of the entries 1000 times larger: a 2-bit exponent either clips the outliers or
+    # flushes the bulk to zero, 4 or 5 exponent bits keep both
+    wide = (rng.standard_normal(20000) * np.where(rng.random(20000) < 0.01, 1000.0, 1.0)).astype(np.float32)
+    _, best_w = oracle.search(wide, FP8_ENCODINGS, 111)
+    assert FP8_ENCODINGS[best_w[0]][0] >= 4
