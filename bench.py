@@ -28,6 +28,8 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_FP8_TFLOPS = 5000.0    # MI355X dense fp8 MFMA (also the rate of fp8 x fp4)
 PEAK_HBM_GBS = 8000.0
+ALU_LANE_RATE = 256 * 4 * 16 * 2.4e9   # vector instructions per lane and second: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
+SEARCH_OPS = 11                        # vector instructions per element and candidate in the search kernel's inner loop
 # HBM-side bytes per layer launch from the two hardware-counter passes whose summary is
 # profiles/cfg5_step_hbm_traffic_pmc.txt (25.77 MB fetched + 34.70 MB written); a profiler figure, not
 # measurable from inside this script, hence only for the workload and mode it was taken on.
@@ -322,6 +324,29 @@ def main():
             singles[cname] = entry
             del xs, w, cb, yb, wsb
         out["single_layers"] = singles
+        # encoding / bias search of Section V-A on one activation tensor (8 x 320 x 64 x 64): 4 FP8 encodings x 111
+        # bias candidates; bound by vector ALU work (see the design notes for the instruction count behind the peak)
+        xs = synth.activations_torch((8, 320, 64, 64), 3, dev).reshape(-1)
+        encs = [(2, 5), (3, 4), (4, 3), (5, 2)]
+        s_mse = torch.empty(4 * 111, dtype=torch.float32, device=dev)
+        s_res = torch.zeros(40, dtype=torch.uint8, device=dev)
+        s_ws = torch.empty(B.fpq_search_workspace_size(xs.numel(), 4, 111), dtype=torch.uint8, device=dev)
+        B.fpq_search_format(xs, encs, 111, s_mse, s_res, s_ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            B.fpq_search_format(xs, encs, 111, s_mse, s_res, s_ws)
+        e1.record()
+        e1.synchronize()
+        s_ms = e0.elapsed_time(e1) / 5
+        r = B.search_result(s_res)
+        evals = xs.numel() * 444 / (s_ms * 1e-3)
+        out["format_search"] = {"elements": xs.numel(), "candidates": 444, "ms": round(s_ms, 3),
+                                "Gevals/s": round(evals / 1e9, 1), "alu_peak_Gevals/s": round(ALU_LANE_RATE / SEARCH_OPS / 1e9, 1),
+                                "frac": round(evals / (ALU_LANE_RATE / SEARCH_OPS), 4),
+                                "chosen": "E%dM%d, max value %.4g (bias %.3f), mse %.3e" % (r.ebits, r.mbits, r.maxval,
+                                                                                          r.real_bias, r.mse)}
+        del xs
         # activation-quantize bandwidth: 64 Mi elements per launch, rotating over 8 buffers (2.7 GB) so that the
         # last-level cache cannot serve the reads; algorithmic bytes = 5 per element (4 read + 1 written)
         n = 64 << 20
@@ -366,6 +391,14 @@ def main():
             oracle.conv2d(xq, FX, sx, wq, FW8, sw, stride=1, pad=1, pix=pix)
             t_cpu += time.perf_counter() - t0
             fl_cpu += 2.0 * (M if pix is None else len(pix)) * wshape[0] * wshape[1] * 9
+        if "format_search" in out:
+            xs_h = synth.activations((65536,), 3)
+            t0 = time.perf_counter()
+            oracle.search(xs_h, [(2, 5), (3, 4), (4, 3), (5, 2)], 111)
+            t_s = time.perf_counter() - t0
+            out["format_search"]["oracle_Gevals/s"] = round(65536 * 444 / t_s / 1e9, 4)
+            out["format_search"]["oracle_sample"] = "65536 elements x 444 candidates on %d host cores, %.1f s" % (
+                oracle.num_threads(), t_s)
         out["cpu_baseline"] = {"value": round(fl_cpu / t_cpu / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
                                "kind": "oracle",
                                "sample": "oracle absmax + quantize + pack + conv2d, W8A8: the config-2 and config-4 convs in "

@@ -101,6 +101,37 @@ size_t fpq_absmax_workspace_size(size_t n);
 int fpq_absmax(const float *x, size_t n, float maxval, float *absmax_out, float *scale_out,
                void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- encoding and bias selection: Section V-A, Algorithm 1 ------------------------------- */
+
+/* Result of fpq_search_format (device memory, 40 bytes).  The chosen candidate is the encoding
+ * (ebits, mbits) with max value maxval; its real-valued bias is real_bias (Eq. (7) solved for b).
+ * To quantize with it, pass the format (ebits, mbits, int_bias, 0) and the scale to fpq_quantize /
+ * fpq_gemm / fpq_conv2d: the grid of the real-valued bias is the grid of int_bias times scale. */
+typedef struct fpq_search_result {
+    int32_t encoding;   /* index into the encodings passed in */
+    int32_t bias_index; /* j of the max-value candidate c_j */
+    int32_t ebits, mbits;
+    int32_t int_bias;   /* 2^(ebits-1) */
+    float maxval;       /* c_j = absmax * (j + 1) / n_bias */
+    float scale;        /* c_j / Eq. (7)(ebits, mbits, int_bias) */
+    float real_bias;
+    float mse;          /* mean squared error of the chosen candidate */
+    int32_t reserved;
+} fpq_search_result;
+
+/* For each of n_enc encodings (ebits[i], mbits[i]; host arrays, n_enc <= 8) and each of n_bias
+ * max-value candidates c_j = absmax(x) * (j + 1) / n_bias (n_bias <= 128; the paper uses 111):
+ * the mean over the tensor of (x - dequantize(quantize(x)))^2, written to mse_out[i * n_bias + j]
+ * (device, may be NULL); result receives the first candidate with the smallest error in the order
+ * of Algorithm 1 (encodings outer, biases inner; the printed initial value prev_mse = 0 is read as
+ * +infinity).  An all-zero tensor is searched as if absmax were 1.  One read of x; errors are summed
+ * in fp32 per wavefront and round and in fp64 across them.  workspace: fpq_search_workspace_size
+ * bytes, 256-byte aligned. */
+size_t fpq_search_workspace_size(size_t n, int n_enc, int n_bias);
+int fpq_search_format(const float *x, size_t n, const int32_t *ebits, const int32_t *mbits, int n_enc,
+                      int n_bias, float *mse_out, fpq_search_result *result, void *workspace,
+                      size_t workspace_bytes, void *stream);
+
 /* ---- activation quantizer: Eq. (6) clip, Eq. (9) step, Eq. (8) round-to-nearest(-even), clip - */
 
 /* x[n] fp32 -> codes, same element order.  n == 0 is a no-op. */

@@ -76,6 +76,10 @@ def lib():
     L.fpq_conv2d_workspace_size.argtypes = [i64, i64, i64, i64, i64, i32, i32, i32, i32, i32]
     L.fpq_conv2d.restype = i32
     L.fpq_conv2d.argtypes = ([vp, i32, F, fl, f32p, vp, F, f32p, f32p, f32p] + [i64] * 5 + [i32] * 5 + [vp, sz, vp])
+    L.fpq_search_workspace_size.restype = sz
+    L.fpq_search_workspace_size.argtypes = [sz, i32, i32]
+    L.fpq_search_format.restype = i32
+    L.fpq_search_format.argtypes = [f32p, sz, vp, vp, i32, i32, f32p, vp, vp, sz, vp]
     _lib = L
     return L
 
@@ -83,7 +87,7 @@ def lib():
 EXPORTS = ["fpq_strerror", "fpq_format_max", "fpq_format_check", "fpq_bias_to_scale", "fpq_code_bytes",
            "fpq_absmax_workspace_size", "fpq_absmax", "fpq_quantize", "fpq_padded_channels", "fpq_quantize_nhwc",
            "fpq_dequantize", "fpq_packed_size", "fpq_pack_weights", "fpq_gemm_workspace_size", "fpq_gemm",
-           "fpq_conv2d_workspace_size", "fpq_conv2d"]
+           "fpq_conv2d_workspace_size", "fpq_conv2d", "fpq_search_workspace_size", "fpq_search_format"]
 
 
 def fmt(f):
@@ -149,6 +153,31 @@ def fpq_conv2d_workspace_size(B, Cin, H, W, Cout, kh, kw, stride, pad, x_is_fp32
 
 
 # ---- device entry points (torch tensors in, status checked)
+
+class fpq_search_result(C.Structure):
+    _fields_ = [("encoding", C.c_int32), ("bias_index", C.c_int32), ("ebits", C.c_int32), ("mbits", C.c_int32),
+                ("int_bias", C.c_int32), ("maxval", C.c_float), ("scale", C.c_float), ("real_bias", C.c_float),
+                ("mse", C.c_float), ("reserved", C.c_int32)]
+
+
+def fpq_search_workspace_size(n, n_enc, n_bias):
+    return lib().fpq_search_workspace_size(n, int(n_enc), int(n_bias))
+
+
+def fpq_search_format(x, encodings, n_bias, mse_out, result, workspace):
+    """encodings: [(e, m), ...]; mse_out: float32 tensor [n_enc * n_bias] or None; result: uint8 tensor of 40 bytes
+    (read it back with search_result())."""
+    ee = (C.c_int32 * len(encodings))(*[int(e) for e, _ in encodings])
+    mm = (C.c_int32 * len(encodings))(*[int(m) for _, m in encodings])
+    _check(lib().fpq_search_format(_ptr(x), x.numel(), C.cast(ee, C.c_void_p), C.cast(mm, C.c_void_p), len(encodings),
+                                   int(n_bias), _ptr(mse_out), _ptr(result), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream()), "fpq_search_format")
+
+
+def search_result(result):
+    """Device result buffer of fpq_search_format -> fpq_search_result (synchronises)."""
+    return fpq_search_result.from_buffer_copy(bytes(result.cpu().numpy().tobytes()[:C.sizeof(fpq_search_result)]))
+
 
 def fpq_absmax(x, maxval, absmax_out, scale_out, workspace):
     _check(lib().fpq_absmax(_ptr(x), x.numel(), float(maxval), _ptr(absmax_out), _ptr(scale_out), _ptr(workspace),

@@ -251,6 +251,44 @@ int fpq_pack_weights(const float* w, int64_t N, int64_t Cin, int kh, int kw, fpq
                                static_cast<uint8_t*>(packed) + kPackedRowsOffset, scale_out, codes_out, s);
 }
 
+// workspace of the search: [1024 partial maxima][absmax, 256 bytes][per-block error sums]
+size_t fpq_search_workspace_size(size_t n, int n_enc, int n_bias)
+{
+    if (n_enc < 1 || n_enc > kSearchMaxEncodings || n_bias < 1 || n_bias > 128) return 0;
+    const int nb = search_blocks(n);
+    return 4096 + 256 + align_up((size_t)(nb > 0 ? nb : 1) * (size_t)(n_enc * n_bias) * sizeof(float), 256);
+}
+
+int fpq_search_format(const float* x, size_t n, const int32_t* ebits, const int32_t* mbits, int n_enc, int n_bias,
+                      float* mse_out, fpq_search_result* result, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (n_enc < 1 || n_enc > kSearchMaxEncodings || n_bias < 1 || n_bias > 128) return FPQ_ERR_SHAPE;
+    if (!ebits || !mbits || !result || !workspace || (n && !x)) return FPQ_ERR_NULL;
+    SearchArgs a;
+    memset(&a, 0, sizeof a);
+    a.n_enc = n_enc;
+    a.J = n_bias;
+    for (int i = 0; i < n_enc; ++i) {
+        const int e = ebits[i], m = mbits[i];
+        if (e < 1 || m < 0 || 1 + e + m > 8) return FPQ_ERR_FORMAT;
+        a.enc[i].e = e;
+        a.enc[i].m = m;
+        a.enc[i].b0 = 1 << (e - 1);
+        a.enc[i].c0 = fpq_format_max(e, m, a.enc[i].b0);
+    }
+    if (workspace_bytes < fpq_search_workspace_size(n, n_enc, n_bias)) return FPQ_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255) || (reinterpret_cast<uintptr_t>(x) & 3) ||
+        (reinterpret_cast<uintptr_t>(result) & 3))
+        return FPQ_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float* maxparts = static_cast<float*>(workspace);
+    float* absmax = maxparts + 1024;
+    float* partial = absmax + 64;
+    int st = launch_absmax(x, n, 1.0f, absmax, nullptr, maxparts, s);
+    if (st) return st;
+    return launch_search(x, n, a, absmax, partial, mse_out, result, s);
+}
+
 size_t fpq_gemm_workspace_size(int64_t M, int64_t N, int64_t K, int x_is_fp32)
 {
     if (M <= 0 || K <= 0 || N <= 0) return 0;

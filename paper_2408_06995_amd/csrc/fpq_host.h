@@ -143,6 +143,26 @@ static inline size_t split_workspace_bytes(const GemmPlan& p, int64_t M, int64_t
     return p.splits > 1 ? (size_t)p.splits * (size_t)M * (size_t)N * sizeof(float) : 0;
 }
 
+// Encoding / bias search (Section V-A): at most 8 encodings x 128 bias candidates.
+constexpr int kSearchMaxEncodings = 8;
+constexpr int kSearchMaxCandidates = 1024;
+struct SearchEnc {
+    int32_t e, m, b0;   // b0 = 2^(e-1)
+    float c0;           // Eq. (7) at b0
+};
+struct SearchArgs {
+    int32_t n_enc, J;
+    SearchEnc enc[kSearchMaxEncodings];
+};
+// Blocks of the search pass: 2048 elements per block and round, at most 1024 blocks.
+static inline int search_blocks(size_t n)
+{
+    size_t g = (n + 2047) / 2048;
+    return (int)(g > 1024 ? 1024 : g);
+}
+int launch_search(const float* x, size_t n, const SearchArgs& a, const float* absmax_dev, float* partial,
+                  float* mse_out, fpq_search_result* result, hipStream_t st);
+
 int launch_absmax(const float* x, size_t n, float maxval, float* absmax_out, float* scale_out, float* partial,
                   hipStream_t st);
 int launch_absmax_partials(const float* x, size_t n, float* partial, hipStream_t st);

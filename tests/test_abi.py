@@ -97,6 +97,18 @@ def test_argument_validation_without_gpu():
     assert L.fpq_gemm(p, 1, f, 1.0, None, p, f, p, None, p, 8, 8, 32, 0, None, 0, None) == -6
     assert L.fpq_gemm(p, 2, f, 0.0, None, p, f, p, None, p, 8, 8, 32, 0, None, 0, None) == -6   # dynamic scale: no sx needed
     assert L.fpq_gemm(p, 3, f, 1.0, None, p, f, p, None, p, 8, 8, 32, 0, None, 0, None) == -8
+    # encoding / bias search: every check below returns before a launch
+    import ctypes as CT
+    ee, mm = (CT.c_int32 * 2)(4, 5), (CT.c_int32 * 2)(3, 2)
+    bad = (CT.c_int32 * 2)(4, 6)
+    ev, mv, bv = CT.cast(ee, CT.c_void_p), CT.cast(mm, CT.c_void_p), CT.cast(bad, CT.c_void_p)
+    assert L.fpq_search_format(p, 100, ev, mv, 0, 111, None, p, p, 1 << 20, None) == -4
+    assert L.fpq_search_format(p, 100, ev, mv, 2, 129, None, p, p, 1 << 20, None) == -4
+    assert L.fpq_search_format(p, 100, ev, mv, 2, 111, None, None, p, 1 << 20, None) == -1
+    assert L.fpq_search_format(p, 100, ev, bv, 2, 111, None, p, p, 1 << 20, None) == -2
+    assert L.fpq_search_format(p, 100, ev, mv, 2, 111, None, p, p, 64, None) == -6
+    assert B.fpq_search_workspace_size(5000, 4, 111) == 4096 + 256 + 3 * 444 * 4 + (256 - 3 * 444 * 4 % 256) % 256
+    assert B.fpq_search_workspace_size(5000, 9, 111) == 0
     assert B.fpq_gemm_workspace_size(8, 8, 32, 2) == B.fpq_gemm_workspace_size(8, 8, 32, 1) + 4096 + 256
     assert L.fpq_gemm(p, 0, e2m1, 1.0, None, p, f, p, None, p, 8, 8, 32, 0, None, 0, None) == -8
     assert L.fpq_gemm(p, 0, B.fmt(synth.E3M4), 1.0, None, p, f, p, None, p, 8, 8, 32, 1, None, 0, None) == -8
