@@ -65,6 +65,13 @@ typedef enum fpq_status {
  *   below it, so the error bound is 7 * 2^-13 * sum|a_k b_k| instead. */
 typedef enum fpq_acc_mode { FPQ_ACC_FP32 = 0, FPQ_ACC_FP8_MFMA = 1 } fpq_acc_mode;
 
+/* May be OR-ed into the acc_mode argument of fpq_gemm / fpq_conv2d: the layer's result (bias included) is
+ * added to what y holds instead of replacing it.  A convolution over a channel-wise concatenation whose
+ * parts are quantized separately, each with its own per-tensor scale (Section VI-A: the skip connection
+ * and the previous layer's output have different value distributions), is then one call per part on that
+ * part's codes and that part's slice of the weights, the second and later calls with this flag. */
+#define FPQ_OUT_ACCUMULATE 0x100
+
 /* What the x argument of fpq_gemm / fpq_conv2d holds (their x_is_fp32 argument).
  * FPQ_X_CODES: codes written by fpq_quantize / fpq_quantize_nhwc with scale sx.
  * FPQ_X_FP32: fp32 activations; the library quantizes them first with the given scale sx / sx_dev.

@@ -13,6 +13,7 @@ LIB_PATH = os.environ.get("FPQ_LIB_PATH") or os.path.join(HERE, "libfpq.so")   #
 
 FPQ_ACC_FP32 = 0
 FPQ_ACC_FP8_MFMA = 1
+FPQ_OUT_ACCUMULATE = 0x100
 FPQ_X_CODES = 0
 FPQ_X_FP32 = 1
 FPQ_X_FP32_DYNAMIC = 2

@@ -315,6 +315,8 @@ static int run_layer(const void* x, int x_is_fp32, fpq_format_t fx, float sx, co
                      int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh, int kw, int stride, int pad,
                      int conv_out, int acc_mode, void* workspace, size_t workspace_bytes, void* stream)
 {
+    const int accumulate = (acc_mode & FPQ_OUT_ACCUMULATE) ? 1 : 0;
+    acc_mode &= ~FPQ_OUT_ACCUMULATE;
     QParams qx, qw;
     int st = resolve_format(fx, &qx);
     if (st) return st;
@@ -405,6 +407,7 @@ static int run_layer(const void* x, int x_is_fp32, fpq_format_t fx, float sx, co
     a.xe = fx.ebits; a.xm = fx.mbits; a.xb = fx.bias;
     a.we = fw.ebits; a.wm = fw.mbits; a.wb = fw.bias;
     a.acc_mode = acc_mode;
+    a.accumulate = accumulate;
     a.partial = partial;
     a.splits = plan.splits;
     a.tile = plan.tile;

@@ -77,6 +77,7 @@ struct GemmArgs {
     float* partial;         // split-K: splits x [M*N] partial results (null: no split)
     int splits;             // number of K slices (>= 1)
     int tile;               // GemmTile chosen by plan_gemm
+    int accumulate;         // 1: add the result to y instead of storing it
 };
 
 // Kernel family / tile for a problem, and how many K slices share an output tile.

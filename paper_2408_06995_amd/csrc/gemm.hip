@@ -289,7 +289,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int m = m0 + wp * TP + 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
-                    if (m < a.M) a.y[(size_t)m * a.N + n] = acc[i][j][r] * sc + bv;
+                    if (m < a.M) {
+                        float* yp = a.y + (size_t)m * a.N + n;
+                        *yp = acc[i][j][r] * sc + bv + (a.accumulate ? *yp : 0.0f);
+                    }
                 }
         }
     } else {
@@ -310,7 +313,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a)
                     if (n < a.N) {
                         const float sc = sxa * a.sw[n];
                         const float bv = a.bias ? a.bias[n] : 0.0f;
-                        ybase[(size_t)n * hw] = acc[i][j][r] * sc + bv;
+                        float* yp = ybase + (size_t)n * hw;
+                        *yp = acc[i][j][r] * sc + bv + (a.accumulate ? *yp : 0.0f);
                     }
                 }
         }

@@ -465,7 +465,9 @@ __global__ __launch_bounds__(256, ((BX <= 128 && NSTAGE <= 2) ? 2 : 1)) void gem
         const bool full = (m0 + BX <= a.M) && (n0 + BW <= a.N);   // whole tile inside the output
         const int mw = m0 + wave * TX;                           // first row of this wave
         const int hw = CONV ? a.Ho * a.Wo : 4;
-        const bool vec = full && ((hw & 3) == 0) && ((reinterpret_cast<uintptr_t>(yout) & 15) == 0);
+        // adding to y (not to split-K partials, which the reduction adds to y) takes the element-wise path
+        const bool accum = a.accumulate && a.splits == 1;
+        const bool vec = full && !accum && ((hw & 3) == 0) && ((reinterpret_cast<uintptr_t>(yout) & 15) == 0);
         if (vec) {
             const int qa = l32 >> 2, qb = l32 & 3;
             const bool b0 = qb & 1, b1 = qb & 2;
@@ -548,7 +550,10 @@ __global__ __launch_bounds__(256, ((BX <= 128 && NSTAGE <= 2) ? 2 : 1)) void gem
 #pragma unroll
                 for (int j = 0; j < NI; ++j) {
                     const int n = n0 + 32 * j + l32;
-                    if (n < a.N) yout[base + (size_t)n * nstride] = acc[i][j][r] * sc[j] + bv[j];
+                    if (n < a.N) {
+                        float* yp = yout + base + (size_t)n * nstride;
+                        *yp = acc[i][j][r] * sc[j] + bv[j] + (accum ? *yp : 0.0f);
+                    }
                 }
             }
         return false;
@@ -639,9 +644,9 @@ __global__ __launch_bounds__(256, ((BX <= 128 && NSTAGE <= 2) ? 2 : 1)) void gem
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // no load may land in LDS after the workgroup has gone
 }
 
-// y[i] = sum over slices of partial[s][i]
+// y[i] = sum over slices of partial[s][i] (+ what y[i] held when the layer accumulates)
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, size_t n, int splits,
-                                                            float* __restrict__ y)
+                                                            int accumulate, float* __restrict__ y)
 {
     const size_t nthreads = (size_t)gridDim.x * 256;
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -653,12 +658,17 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
                 const float4 v = reinterpret_cast<const float4*>(partial + (size_t)s * n)[i];
                 acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
             }
+            if (accumulate) {
+                const float4 v = reinterpret_cast<const float4*>(y)[i];
+                acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+            }
             reinterpret_cast<float4*>(y)[i] = acc;
         }
     } else {
         for (; i < n; i += nthreads) {
             float acc = partial[i];
             for (int s = 1; s < splits; ++s) acc += partial[(size_t)s * n + i];
+            if (accumulate) acc += y[i];
             y[i] = acc;
         }
     }
@@ -686,7 +696,8 @@ static int launch_dma_one(const GemmArgs& a, hipStream_t st)
         size_t grid = (n / 4 + 255) / 256;
         if (grid < 1) grid = 1;
         if (grid > 4096) grid = 4096;
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)grid), dim3(256), 0, st, a.partial, n, a.splits, a.y);
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)grid), dim3(256), 0, st, a.partial, n, a.splits, a.accumulate,
+                           a.y);
     }
     return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
 }

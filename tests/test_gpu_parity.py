@@ -433,3 +433,59 @@ def test_conv_large_tile_and_split_k(case, fxn, fwn, acc):
     y, (sx, xq, wq, sw) = run_conv(x, w, h, fx, fw, stride, pad, acc, bias)
     Y, T = oracle.conv2d(xq, fx, sx, wq, fw, sw, bias, stride=stride, pad=pad)
     check_close(y, Y, T, rel=REL_FP8_MFMA if acc else 1e-5, what="large-tile conv %s" % ((case, fxn, fwn, acc),))
+
+
+# ------------------------------------------------------------------------------ separately quantized concatenation
+
+@pytest.mark.parametrize("case", [("conv", 2, 24, 40, 9, 9, 48, 3), ("conv", 1, 320, 640, 32, 32, 320, 1),
+                                  ("conv", 2, 640, 640, 8, 8, 320, 3), ("linear", 300, 64, 96, 130),
+                                  ("linear", 512, 2560, 2560, 320)])
+@pytest.mark.parametrize("acc", [B.FPQ_ACC_FP32, B.FPQ_ACC_FP8_MFMA])
+def test_concatenated_input_with_one_scale_per_part(case, acc):
+    """Section VI-A: the two halves of a channel-wise concatenation are quantized separately, each with its own
+    per-tensor scale.  One call per half on that half's codes and weight slice, the second adding to y
+    (FPQ_OUT_ACCUMULATE), must give the sum of the oracle's two layers."""
+    fx, fw = synth.E4M3, synth.E4M3
+    if case[0] == "conv":
+        _, Bn, Ca, Cb, H, W, Cout, k = case
+        a = synth.activations((Bn, Ca, H, W), 21)
+        b = (synth.activations((Bn, Cb, H, W), 22) * np.float32(7.0)).astype(np.float32)   # another value range
+        w = synth.weights((Cout, Ca + Cb, k, k), 23)
+        parts = [(a, w[:, :Ca].copy()), (b, w[:, Ca:].copy())]
+        N = Cout
+    else:
+        _, M, Ka, Kb, N = case
+        a = synth.activations((M, Ka), 21)
+        b = (synth.activations((M, Kb), 22) * np.float32(7.0)).astype(np.float32)
+        w = synth.weights((N, Ka + Kb), 23)
+        parts = [(a, w[:, :Ka].copy()), (b, w[:, Ka:].copy())]
+    # one weight scale per output channel over the whole (concatenated) row
+    sw = (np.abs(w.reshape(N, -1)).max(axis=1) / np.float32(fw[3])).astype(np.float32)
+    bias = np.linspace(-0.5, 0.5, N).astype(np.float32)
+    y = None
+    Ysum, Tsum = 0.0, 0.0
+    for idx, (x, wp) in enumerate(parts):
+        sx = oracle.scale_from_absmax(oracle.absmax(x), fx[3])
+        xq = oracle.quantize(x, fx, sx)
+        wq, sw_o = oracle.pack_weights(wp, fw, None, sw)
+        packed, sw_t, _ = gpu_pack(wp, fw, None, sw)
+        flags = acc | (B.FPQ_OUT_ACCUMULATE if idx else 0)
+        bias_t = dev(bias) if idx == 0 else None
+        if case[0] == "conv":
+            Y, T = oracle.conv2d(xq, fx, sx, wq, fw, sw_o, bias if idx == 0 else None, stride=1, pad=k // 2)
+            if y is None:
+                y = torch.full((Bn, Cout, H, W), float("nan"), dtype=torch.float32, device=DEV)
+            ws = torch.empty(B.fpq_conv2d_workspace_size(Bn, x.shape[1], H, W, Cout, k, k, 1, k // 2, 1), dtype=torch.uint8,
+                             device=DEV)
+            B.fpq_conv2d(dev(x), 1, fx, sx, None, packed, fw, sw_t, bias_t, y, Bn, x.shape[1], H, W, Cout, k, k, 1, k // 2,
+                         flags, ws)
+        else:
+            Y, T = oracle.gemm(xq, fx, sx, wq, fw, sw_o, bias if idx == 0 else None)
+            if y is None:
+                y = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+            ws = torch.empty(max(256, B.fpq_gemm_workspace_size(M, N, x.shape[1], 1)), dtype=torch.uint8, device=DEV)
+            B.fpq_gemm(dev(x), 1, fx, sx, None, packed, fw, sw_t, bias_t, y, M, N, x.shape[1], flags, ws)
+        Ysum = Ysum + Y
+        Tsum = Tsum + T
+    torch.cuda.synchronize()
+    check_close(y.cpu().numpy(), Ysum, Tsum, rel=REL_FP8_MFMA if acc else 1e-5, what="split concat %s acc %d" % (case, acc))
