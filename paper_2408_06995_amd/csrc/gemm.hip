@@ -16,6 +16,8 @@
 //   ACC_FP8_MFMA  codes are fed to the 8-bit / 4-bit MFMA (32x32x64) directly.
 // K ordering inside a 128-code step is private to this file: any order is valid as long as both
 // operands use the same one, and each back end picks the order its register layout wants.
+#include <type_traits>
+
 #include "gemm_common.h"
 
 namespace fpq {
@@ -276,49 +278,59 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a)
 
     // ---- epilogue
     const float sxa = (a.sx_dev ? a.sx_dev[0] : a.sx) * a.alpha;
-    if (!CONV) {
-        // P = activations: acc[i][j][r] is (m, n) = (row block i, r -> 8(r/4) + 4g + r%4 ; lane -> n)
+    // two copies of the stores, chosen once (with the choice per element the compiler loads y ahead of every
+    // store, also when nothing is added)
+    auto store_all = [&](auto add_to_y) {
+        auto put = [&](float* yp, float v) {
+            if constexpr (decltype(add_to_y)::value)
+                *yp = v + *yp;
+            else
+                *yp = v;
+        };
+        if (!CONV) {
+            // P = activations: acc[i][j][r] is (m, n) = (row block i, r -> 8(r/4) + 4g + r%4 ; lane -> n)
 #pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int n = n0 + wq * TQ + 32 * j + l32;
-            if (n >= a.N) continue;
-            const float sc = sxa * a.sw[n];
-            const float bv = a.bias ? a.bias[n] : 0.0f;
+            for (int j = 0; j < NI; ++j) {
+                const int n = n0 + wq * TQ + 32 * j + l32;
+                if (n >= a.N) continue;
+                const float sc = sxa * a.sw[n];
+                const float bv = a.bias ? a.bias[n] : 0.0f;
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
+                for (int i = 0; i < MI; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = m0 + wp * TP + 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
-                    if (m < a.M) {
-                        float* yp = a.y + (size_t)m * a.N + n;
-                        *yp = acc[i][j][r] * sc + bv + (a.accumulate ? *yp : 0.0f);
+                    for (int r = 0; r < 16; ++r) {
+                        const int m = m0 + wp * TP + 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
+                        if (m < a.M) put(a.y + (size_t)m * a.N + n, acc[i][j][r] * sc + bv);
                     }
-                }
-        }
-    } else {
-        // P = weights: rows are n, lanes are pixels m
-        const int hw = a.Ho * a.Wo;
+            }
+        } else {
+            // P = weights: rows are n, lanes are pixels m
+            const int hw = a.Ho * a.Wo;
 #pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int m = m0 + wq * TQ + 32 * j + l32;
-            if (m >= a.M) continue;
-            const int bi = m / hw;
-            const int pix = m - bi * hw;
-            float* ybase = a.y + (size_t)bi * a.N * hw + pix;
+            for (int j = 0; j < NI; ++j) {
+                const int m = m0 + wq * TQ + 32 * j + l32;
+                if (m >= a.M) continue;
+                const int bi = m / hw;
+                const int pix = m - bi * hw;
+                float* ybase = a.y + (size_t)bi * a.N * hw + pix;
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
+                for (int i = 0; i < MI; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int n = n0 + wp * TP + 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
-                    if (n < a.N) {
-                        const float sc = sxa * a.sw[n];
-                        const float bv = a.bias ? a.bias[n] : 0.0f;
-                        float* yp = ybase + (size_t)n * hw;
-                        *yp = acc[i][j][r] * sc + bv + (a.accumulate ? *yp : 0.0f);
+                    for (int r = 0; r < 16; ++r) {
+                        const int n = n0 + wp * TP + 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
+                        if (n < a.N) {
+                            const float sc = sxa * a.sw[n];
+                            const float bv = a.bias ? a.bias[n] : 0.0f;
+                            put(ybase + (size_t)n * hw, acc[i][j][r] * sc + bv);
+                        }
                     }
-                }
+            }
         }
-    }
+    };
+    if (a.accumulate)
+        store_all(std::true_type{});
+    else
+        store_all(std::false_type{});
 }
 
 // ---------------------------------------------------------------------------------- dispatch

@@ -19,6 +19,8 @@
 //
 // Split-K: the K steps of an output tile can be cut into slices; slice s writes its scaled partial
 // sums to partial[s] and a second kernel adds the slices into y.
+#include <type_traits>
+
 #include "gemm_common.h"
 
 namespace fpq {
@@ -531,31 +533,43 @@ __global__ __launch_bounds__(256, ((BX <= 128 && NSTAGE <= 2) ? 2 : 1)) void gem
             sc[j] = sxa * stab[32 * j + l32];
             bv[j] = stab[256 + 32 * j + l32];
         }
+        // two copies of the loop, chosen once: with the choice inside, the compiler loads y ahead of every store
+        // (the store makes the address known to be valid), which serialises the plain case as well
+        auto element_wise = [&](auto add_to_y) {
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+            for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = mw + 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
-                if (m >= a.M) continue;
-                size_t base;
-                size_t nstride;
-                if (CONV) {
-                    const int bi = m / hw;
-                    base = (size_t)bi * a.N * hw + (m - bi * hw);
-                    nstride = (size_t)hw;
-                } else {
-                    base = (size_t)m * a.N;
-                    nstride = 1;
-                }
+                for (int r = 0; r < 16; ++r) {
+                    const int m = mw + 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
+                    if (m >= a.M) continue;
+                    size_t base;
+                    size_t nstride;
+                    if (CONV) {
+                        const int bi = m / hw;
+                        base = (size_t)bi * a.N * hw + (m - bi * hw);
+                        nstride = (size_t)hw;
+                    } else {
+                        base = (size_t)m * a.N;
+                        nstride = 1;
+                    }
 #pragma unroll
-                for (int j = 0; j < NI; ++j) {
-                    const int n = n0 + 32 * j + l32;
-                    if (n < a.N) {
-                        float* yp = yout + base + (size_t)n * nstride;
-                        *yp = acc[i][j][r] * sc[j] + bv[j] + (accum ? *yp : 0.0f);
+                    for (int j = 0; j < NI; ++j) {
+                        const int n = n0 + 32 * j + l32;
+                        if (n < a.N) {
+                            float* yp = yout + base + (size_t)n * nstride;
+                            const float v = acc[i][j][r] * sc[j] + bv[j];
+                            if constexpr (decltype(add_to_y)::value)
+                                *yp = v + *yp;
+                            else
+                                *yp = v;
+                        }
                     }
                 }
-            }
+        };
+        if (accum)
+            element_wise(std::true_type{});
+        else
+            element_wise(std::false_type{});
         return false;
     };
 
