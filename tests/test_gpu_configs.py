@@ -81,7 +81,12 @@ def check_layer(L, x, w, h, fx, fw, accs, n_random=64, seed=0, full=False):
                 hw = yv.shape[2]
                 got_y = yv[pos // hw, :, pos % hw]
         else:
-            assert np.array_equal(ws.cpu().numpy()[:L.M * L.K].reshape(L.M, L.K), xq), "activation codes"
+            # small linear layers quantize inside the layer kernel's loader and leave no codes behind: check
+            # the quantizer on its own with the scale the call published
+            qc = torch.empty(L.M * L.K, dtype=torch.uint8, device=DEV)
+            B.fpq_quantize(x_t, fx, 0.0, ws[-256:-252].view(torch.float32), qc)
+            torch.cuda.synchronize()
+            assert np.array_equal(qc.cpu().numpy().reshape(L.M, L.K), xq), "activation codes"
             yv = y.cpu().numpy().reshape(L.M, L.N)
             got_y = yv if full else yv[pos]
         assert not np.isnan(y.cpu().numpy()).any(), "unwritten outputs"
