@@ -381,7 +381,27 @@ def main():
         a_gbs = 4.0 * n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
         out["quantize"] = {"elements": n, "GB/s": round(q_gbs, 1), "frac_of_hbm_peak": round(q_gbs / PEAK_HBM_GBS, 4),
                            "absmax_GB/s": round(a_gbs, 1), "absmax_frac": round(a_gbs / PEAK_HBM_GBS, 4)}
-        del bufs, codes
+        # zero count (sparsity) on the code buffers of 64 Mi elements: one read, 1 B per element; the fp32 form on
+        # the rotating fp32 buffers, 4 B per element
+        zc = torch.zeros(1, dtype=torch.int64, device=dev)
+        zws = torch.empty(B.fpq_count_zeros_workspace_size(n), dtype=torch.uint8, device=dev)
+        cbig = [torch.randint(0, 256, (4 * n,), dtype=torch.uint8, device=dev) for _ in range(4)]   # 256 MiB each
+        B.fpq_count_zeros(cbig[0], B.FPQ_X_CODES, 4 * n, FX, zc, zws)
+        e0.record()
+        for i in range(reps):
+            B.fpq_count_zeros(cbig[i & 3], B.FPQ_X_CODES, 4 * n, FX, zc, zws)
+        e1.record()
+        e1.synchronize()
+        zc_gbs = 4.0 * n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        e0.record()
+        for i in range(reps):
+            B.fpq_count_zeros(bufs[i & 7], B.FPQ_X_FP32, n, None, zc, zws)
+        e1.record()
+        e1.synchronize()
+        zf_gbs = 4.0 * n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        out["zero_count"] = {"code_bytes": 4 * n, "codes_GB/s": round(zc_gbs, 1), "codes_frac": round(zc_gbs / PEAK_HBM_GBS, 4),
+                             "fp32_GB/s": round(zf_gbs, 1), "fp32_frac": round(zf_gbs / PEAK_HBM_GBS, 4)}
+        del bufs, codes, cbig
 
     if not args.no_cpu_baseline:
         import oracle

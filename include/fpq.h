@@ -78,7 +78,7 @@ typedef enum fpq_acc_mode { FPQ_ACC_FP32 = 0, FPQ_ACC_FP8_MFMA = 1 } fpq_acc_mod
  * FPQ_X_FP32_DYNAMIC: fp32 activations and no scale: the library finds the per-tensor scale
  *   absmax(x) / maxval itself (what fpq_absmax computes, bit for bit) on the way; sx and sx_dev are
  *   ignored.  One launch fewer than fpq_absmax followed by FPQ_X_FP32. */
-typedef enum fpq_x_kind { FPQ_X_CODES = 0, FPQ_X_FP32 = 1, FPQ_X_FP32_DYNAMIC = 2 } fpq_x_kind;
+typedef enum fpq_x_kind { FPQ_X_CODES = 0, FPQ_X_FP32 = 1, FPQ_X_FP32_DYNAMIC = 2, FPQ_X_CODES_BYTE = 3 } fpq_x_kind;
 
 const char *fpq_strerror(int status);
 
@@ -138,6 +138,24 @@ size_t fpq_search_workspace_size(size_t n, int n_enc, int n_bias);
 int fpq_search_format(const float *x, size_t n, const int32_t *ebits, const int32_t *mbits, int n_enc,
                       int n_bias, float *mse_out, fpq_search_result *result, void *workspace,
                       size_t workspace_bytes, void *stream);
+
+/* ---- sparsity (Section VI, "Sparsity"): how many values of a tensor are zero ---------------- */
+
+/* Counts the zeros among the n elements of x and writes the count to count_out (one 64-bit unsigned
+ * integer in device memory).  x_kind says what x holds:
+ *   FPQ_X_CODES       codes of format f as fpq_quantize writes them (one per byte; two per byte for
+ *                     formats of at most 4 bits, and then the high nibble of the last byte is not
+ *                     counted when n is odd); a code is zero when its exponent and mantissa fields
+ *                     are, whatever its sign bit;
+ *   FPQ_X_CODES_BYTE  codes of format f, one per byte whatever the format (codes_out of
+ *                     fpq_pack_weights);
+ *   FPQ_X_FP32        fp32 values (+0 and -0 count; f is ignored), for the full-precision tensor the
+ *                     quantized one is compared with.
+ * x needs no alignment beyond that of its element type.  workspace: fpq_count_zeros_workspace_size
+ * bytes, 8-byte aligned; n == 0 writes 0. */
+size_t fpq_count_zeros_workspace_size(size_t n);
+int fpq_count_zeros(const void *x, int x_kind, size_t n, fpq_format_t f, uint64_t *count_out,
+                    void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---- activation quantizer: Eq. (6) clip, Eq. (9) step, Eq. (8) round-to-nearest(-even), clip - */
 

@@ -212,6 +212,22 @@ def conv2d(xq, fx, sx, wq, fw, sw, bias=None, stride=1, pad=0, pix=None):
     return Y, T
 
 
+def count_zeros(values):
+    """Section VI, "Sparsity": the number of values of a tensor that are zero (+0 and -0 alike)."""
+    return int(np.count_nonzero(np.asarray(values) == 0))
+
+
+def count_zero_codes(codes, fmt):
+    """The same on codes (one per byte): every code is decoded (Eq. (5)) and its value compared with zero."""
+    return count_zeros(dequantize(codes, fmt))
+
+
+def sparsity(values):
+    """Fraction of the values that are zero."""
+    v = np.asarray(values)
+    return count_zeros(v) / v.size
+
+
 def search_candidate(absmax, j, J):
     """Section V-A: max-value candidate j of J, evenly spaced in (0, absmax]."""
     return float(lib().oracle_search_candidate(float(absmax), int(j), int(J)))

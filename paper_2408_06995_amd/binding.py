@@ -17,6 +17,7 @@ FPQ_OUT_ACCUMULATE = 0x100
 FPQ_X_CODES = 0
 FPQ_X_FP32 = 1
 FPQ_X_FP32_DYNAMIC = 2
+FPQ_X_CODES_BYTE = 3
 
 
 class fpq_format_t(C.Structure):
@@ -81,6 +82,10 @@ def lib():
     L.fpq_search_workspace_size.argtypes = [sz, i32, i32]
     L.fpq_search_format.restype = i32
     L.fpq_search_format.argtypes = [f32p, sz, vp, vp, i32, i32, f32p, vp, vp, sz, vp]
+    L.fpq_count_zeros_workspace_size.restype = sz
+    L.fpq_count_zeros_workspace_size.argtypes = [sz]
+    L.fpq_count_zeros.restype = i32
+    L.fpq_count_zeros.argtypes = [vp, i32, sz, F, vp, vp, sz, vp]
     _lib = L
     return L
 
@@ -88,7 +93,8 @@ def lib():
 EXPORTS = ["fpq_strerror", "fpq_format_max", "fpq_format_check", "fpq_bias_to_scale", "fpq_code_bytes",
            "fpq_absmax_workspace_size", "fpq_absmax", "fpq_quantize", "fpq_padded_channels", "fpq_quantize_nhwc",
            "fpq_dequantize", "fpq_packed_size", "fpq_pack_weights", "fpq_gemm_workspace_size", "fpq_gemm",
-           "fpq_conv2d_workspace_size", "fpq_conv2d", "fpq_search_workspace_size", "fpq_search_format"]
+           "fpq_conv2d_workspace_size", "fpq_conv2d", "fpq_search_workspace_size", "fpq_search_format",
+           "fpq_count_zeros_workspace_size", "fpq_count_zeros"]
 
 
 def fmt(f):
@@ -178,6 +184,17 @@ def fpq_search_format(x, encodings, n_bias, mse_out, result, workspace):
 def search_result(result):
     """Device result buffer of fpq_search_format -> fpq_search_result (synchronises)."""
     return fpq_search_result.from_buffer_copy(bytes(result.cpu().numpy().tobytes()[:C.sizeof(fpq_search_result)]))
+
+
+def fpq_count_zeros_workspace_size(n):
+    return lib().fpq_count_zeros_workspace_size(n)
+
+
+def fpq_count_zeros(x, x_kind, n, f, count_out, workspace):
+    """x: uint8 codes or float32 values; count_out: int64 tensor of one element (the count is unsigned)."""
+    _check(lib().fpq_count_zeros(_ptr(x), int(x_kind), int(n), fmt(f) if f is not None else fpq_format_t(0, 0, 0, 0.0),
+                                 _ptr(count_out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                 _stream()), "fpq_count_zeros")
 
 
 def fpq_absmax(x, maxval, absmax_out, scale_out, workspace):

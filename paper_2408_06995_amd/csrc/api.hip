@@ -170,6 +170,27 @@ int fpq_absmax(const float* x, size_t n, float maxval, float* absmax_out, float*
                          static_cast<hipStream_t>(stream));
 }
 
+size_t fpq_count_zeros_workspace_size(size_t) { return 1024 * sizeof(unsigned long long); }
+
+int fpq_count_zeros(const void* x, int x_kind, size_t n, fpq_format_t f, uint64_t* count_out, void* workspace,
+                    size_t workspace_bytes, void* stream)
+{
+    if (!count_out || !workspace || (n && !x)) return FPQ_ERR_NULL;
+    if (x_kind != FPQ_X_CODES && x_kind != FPQ_X_FP32 && x_kind != FPQ_X_CODES_BYTE) return FPQ_ERR_UNSUPPORTED;
+    const bool fp32 = x_kind == FPQ_X_FP32;
+    if (!fp32) {
+        int st = fpq_format_check(f);
+        if (st) return st;
+    }
+    if (workspace_bytes < fpq_count_zeros_workspace_size(n)) return FPQ_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 7) || (reinterpret_cast<uintptr_t>(count_out) & 7) ||
+        (fp32 && (reinterpret_cast<uintptr_t>(x) & 3)))
+        return FPQ_ERR_ALIGN;
+    return launch_count_zeros(x, fp32, n, f.ebits + f.mbits, x_kind == FPQ_X_CODES && is_four_bit(f),
+                              reinterpret_cast<unsigned long long*>(count_out),
+                              static_cast<unsigned long long*>(workspace), static_cast<hipStream_t>(stream));
+}
+
 int fpq_quantize(const float* x, size_t n, fpq_format_t f, float scale, const float* scale_dev, uint8_t* codes,
                  void* stream)
 {

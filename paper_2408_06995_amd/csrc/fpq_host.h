@@ -168,6 +168,14 @@ static inline int search_blocks(size_t n)
 int launch_search(const float* x, size_t n, const SearchArgs& a, const float* absmax_dev, float* partial,
                   float* mse_out, fpq_search_result* result, hipStream_t st);
 
+// Zero count (Section VI, "Sparsity"): blocks of the counting pass, each with a contiguous share of the bytes.
+static inline int count_zeros_parts(size_t nbytes)
+{
+    const size_t p = (nbytes + 16383) / 16384;
+    return p < 1 ? 1 : (p > 1024 ? 1024 : (int)p);
+}
+int launch_count_zeros(const void* x, int is_fp32, size_t n, int em, bool four_bit, unsigned long long* out,
+                       unsigned long long* partial, hipStream_t st);
 int launch_absmax(const float* x, size_t n, float maxval, float* absmax_out, float* scale_out, float* partial,
                   hipStream_t st);
 int launch_absmax_partials(const float* x, size_t n, float* partial, hipStream_t st);

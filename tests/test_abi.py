@@ -71,6 +71,7 @@ def test_argument_validation_without_gpu():
     L = B.lib()
     f = B.fmt(synth.E4M3)
     bad = B.fmt((4, 3, 7, 449.0))
+    bad_fmt = bad
     p = C.c_void_p(4096)          # never dereferenced: every call below fails validation first
     assert L.fpq_quantize(p, 16, bad, 1.0, None, p, None) == -2
     assert L.fpq_quantize(p, 16, f, 0.0, None, p, None) == -3
@@ -116,5 +117,14 @@ def test_argument_validation_without_gpu():
     assert L.fpq_gemm(p, 0, f, 1.0, None, p, f, p, None, p, 0, 8, 32, 0, None, 0, None) == 0
     assert L.fpq_conv2d(p, 0, f, 1.0, None, p, f, p, None, p, 1, 16, 2, 2, 8, 3, 3, 1, 0, 0, None, 0, None) == -4
     assert L.fpq_conv2d(p, 0, f, 1.0, None, p, f, p, None, p, 1, 16, 8, 8, 8, 3, 3, 0, 1, 0, None, 0, None) == -4
+    # zero count: null, kind, format, workspace, alignment
+    assert B.fpq_count_zeros_workspace_size(10 ** 9) == 8192
+    assert L.fpq_count_zeros(p, 0, 100, f, None, p, 8192, None) == -1
+    assert L.fpq_count_zeros(None, 0, 100, f, p, p, 8192, None) == -1
+    assert L.fpq_count_zeros(p, 2, 100, f, p, p, 8192, None) == -8
+    assert L.fpq_count_zeros(p, 0, 100, bad_fmt, p, p, 8192, None) == -2
+    assert L.fpq_count_zeros(p, 0, 100, f, p, p, 8184, None) == -6
+    assert L.fpq_count_zeros(p, 0, 100, f, C.c_void_p(4100), p, 8192, None) == -5
+    assert L.fpq_count_zeros(C.c_void_p(4098), 1, 100, f, p, p, 8192, None) == -5
     assert L.fpq_strerror(-2).decode().startswith("invalid ExMy")
     assert L.fpq_strerror(0) == b"ok"

@@ -544,3 +544,46 @@ def test_search_prefers_mantissa_for_uniform_and_exponent_for_wide_range_data():
     mse_w, best_w = oracle.search(wide, FP8_ENCODINGS, 111)
     assert FP8_ENCODINGS[best_w[0]] == (3, 4)
     assert mse_w[1].min() < 0.25 * mse_w[0].min()
+
+
+# ---- sparsity (Section VI, "Sparsity"): zero count
+
+
+@pytest.mark.parametrize("e,m", ALL_EM)
+def test_zero_codes_are_the_two_signed_zeros(e, m):
+    """Of all codes of a format exactly two are zero: field bits all clear, either sign (Eq. (5), p = 0, mantissa 0)."""
+    b = 1 << (e - 1)
+    fmt = (e, m, b, oracle.format_max(e, m, b))
+    ncodes = 1 << (1 + e + m)
+    codes = np.arange(ncodes, dtype=np.uint8)
+    zeros = [c for c in range(ncodes) if oracle.decode(fmt, c) == 0.0]
+    assert zeros == [0, 1 << (e + m)]
+    assert oracle.count_zero_codes(codes, fmt) == 2
+    rep = np.tile(codes, 7)[: 7 * ncodes - 3]
+    expect = sum(1 for c in rep.tolist() if (c & ((1 << (e + m)) - 1)) == 0)
+    assert oracle.count_zero_codes(rep, fmt) == expect
+
+
+def test_fp32_zero_count_includes_minus_zero():
+    v = np.array([0.0, -0.0, 1e-45, -1e-45, 1.0, np.inf], dtype=np.float32)
+    assert oracle.count_zeros(v) == 2
+    assert oracle.sparsity(v) == pytest.approx(2 / 6)
+
+
+@pytest.mark.parametrize("fmt", [synth.E2M1, synth.E4M3, (3, 4, 4, 15.5)])
+def test_sparsity_of_quantized_gaussian_equals_closed_form(fmt):
+    """N(0, sigma^2) values quantized with a fixed scale become zero exactly when |x / scale| <= half the smallest
+    step 2^(1-b-m) (the tie goes to the even neighbour, zero), so the expected sparsity is erf(t / (sigma sqrt 2))."""
+    e, m, b, c = fmt
+    rng = np.random.default_rng(77)
+    n = 1 << 20
+    sigma = 0.02
+    x = (rng.standard_normal(n) * sigma).astype(np.float32)
+    scale = np.float32(4 * sigma / c)            # the clip sits at four sigma
+    codes = oracle.quantize(x, fmt, scale)
+    got = oracle.count_zero_codes(codes, fmt) / n
+    t = 0.5 * 2.0 ** (1 - b - m) * float(scale)
+    p = math.erf(t / (sigma * math.sqrt(2)))
+    assert abs(got - p) < 5 * math.sqrt(p * (1 - p) / n) + 1e-6
+    # the quantized tensor is far sparser than the fp32 one it came from (no exact zeros there)
+    assert oracle.count_zeros(x) == 0 and got > 0
