@@ -302,15 +302,23 @@ def main():
             else:
                 B.fpq_quantize(xs, FX, 0.0, st2[1:2], cb)
             yb = torch.empty(L.M * L.N, dtype=torch.float32, device=dev)
+            yq = torch.empty(L.M * B.fpq_padded_channels(L.N), dtype=torch.uint8, device=dev)
             wsb = torch.empty(max(256, wsz), dtype=torch.uint8, device=dev)
             entry = {}
             for tag, fw in (("w8a8", FW8), ("w4a8", FW4)):
                 pk = torch.empty(B.fpq_packed_size(L.N, L.Cin, kk, kk, fw), dtype=torch.uint8, device=dev)
                 sw = torch.empty(L.N, dtype=torch.float32, device=dev)
                 B.fpq_pack_weights(w, fw, None, None, pk, sw, None)
-                for mname, mode in (("fp32", B.FPQ_ACC_FP32), ("fp8mfma", B.FPQ_ACC_FP8_MFMA)):
+                for mname, mode, q in (("fp32", B.FPQ_ACC_FP32, False), ("fp8mfma", B.FPQ_ACC_FP8_MFMA, False),
+                                       ("fp32_codes_out", B.FPQ_ACC_FP32, True), ("fp8mfma_codes_out", B.FPQ_ACC_FP8_MFMA, True)):
                     def one():
-                        if L.kind == "conv":
+                        if q and L.kind == "conv":      # result quantized for the next layer (E4M3, static scale) in the epilogue
+                            B.fpq_conv2d_codes_out(cb, 0, FX, 0.0, st2[1:2], pk, fw, sw, None, FX, 0.05, None, yq, L.B, L.Cin,
+                                                   L.H, L.W, L.Cout, L.k, L.k, L.stride, L.pad, mode, wsb)
+                        elif q:
+                            B.fpq_gemm_codes_out(cb, 0, FX, 0.0, st2[1:2], pk, fw, sw, None, FX, 0.05, None, yq, L.M, L.N, L.K,
+                                                 mode, wsb)
+                        elif L.kind == "conv":
                             B.fpq_conv2d(cb, 0, FX, 0.0, st2[1:2], pk, fw, sw, None, yb, L.B, L.Cin, L.H, L.W, L.Cout, L.k,
                                          L.k, L.stride, L.pad, mode, wsb)
                         else:
@@ -330,8 +338,27 @@ def main():
                     e1.synchronize()
                     us = e0.elapsed_time(e1) * 1e3 / 64
                     entry["%s_%s" % (tag, mname)] = {"us": round(us, 2), "TFLOP/s": round(synth.flops(L) / us / 1e6, 1)}
+                if L.kind == "linear" and tag == "w8a8":
+                    # what the codes-out form replaces when the next layer is quantized too: the fp32 result written,
+                    # then read again by the next layer's quantize pass (static scale)
+                    def two():
+                        B.fpq_gemm(cb, 0, FX, 0.0, st2[1:2], pk, fw, sw, None, yb, L.M, L.N, L.K, B.FPQ_ACC_FP32, wsb)
+                        B.fpq_quantize(yb, FX, 0.05, None, yq)
+                    two()
+                    torch.cuda.synchronize()
+                    g2 = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g2):
+                        for _ in range(16):
+                            two()
+                    g2.replay()
+                    e0.record()
+                    for _ in range(4):
+                        g2.replay()
+                    e1.record()
+                    e1.synchronize()
+                    entry["w8a8_fp32_then_quantize_us"] = round(e0.elapsed_time(e1) * 1e3 / 64, 2)
             singles[cname] = entry
-            del xs, w, cb, yb, wsb
+            del xs, w, cb, yb, yq, wsb
         out["single_layers"] = singles
         # encoding / bias search of Section V-A on one activation tensor (8 x 320 x 64 x 64): 4 FP8 encodings x 111
         # bias candidates; bound by vector ALU work (see the design notes for the instruction count behind the peak)

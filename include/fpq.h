@@ -224,6 +224,32 @@ int fpq_conv2d(const void *x, int x_is_fp32, fpq_format_t fx, float sx, const fl
                int64_t B, int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh, int kw, int stride,
                int pad, int acc_mode, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- the same layers with the result handed to the next quantized layer as codes -------------
+ *
+ * Section V applies the activation quantizer to the input of every convolution and linear layer, so when
+ * one such layer feeds another, the fp32 result exists only to be quantized again.  These entry points
+ * quantize it in the layer kernel's epilogue instead: yq[m, n] = Q(v; fy, sy) with v the fp32 value
+ * fpq_gemm / fpq_conv2d would have written (sx * sw[n] * sum + bias[n]), Q the activation quantizer of
+ * Eq. (6)-(9) (as fpq_quantize), fy a format stored one code per byte, and sy (or *sy_dev when not
+ * NULL) the next layer's static per-tensor scale.  One byte per output is written instead of four.
+ *
+ * yq: codes, row-major [M, Np] with Np = fpq_padded_channels(N); columns N .. Np - 1 receive code 0;
+ * 16-byte aligned.  For a convolution the rows are the output pixels in (b, ho, wo) order, i.e. the
+ * channels-last buffer [B, Ho, Wo, Np] that fpq_conv2d takes as codes; for a linear layer with
+ * N % 16 == 0 it is the [M, K = N] code matrix that fpq_gemm takes.  All other arguments, the workspace
+ * and its size are those of fpq_gemm / fpq_conv2d; FPQ_OUT_ACCUMULATE is not accepted.  Because v
+ * depends on the summation order within the fp32 tolerance, a code can differ from the one computed
+ * from an exactly rounded v where v lies within that tolerance of a rounding boundary of fy. */
+int fpq_gemm_codes_out(const void *x, int x_is_fp32, fpq_format_t fx, float sx, const float *sx_dev,
+                       const void *packed_w, fpq_format_t fw, const float *sw, const float *bias,
+                       fpq_format_t fy, float sy, const float *sy_dev, uint8_t *yq, int64_t M, int64_t N,
+                       int64_t K, int acc_mode, void *workspace, size_t workspace_bytes, void *stream);
+int fpq_conv2d_codes_out(const void *x, int x_is_fp32, fpq_format_t fx, float sx, const float *sx_dev,
+                         const void *packed_w, fpq_format_t fw, const float *sw, const float *bias,
+                         fpq_format_t fy, float sy, const float *sy_dev, uint8_t *yq, int64_t B,
+                         int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh, int kw, int stride,
+                         int pad, int acc_mode, void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -212,6 +212,22 @@ def conv2d(xq, fx, sx, wq, fw, sw, bias=None, stride=1, pad=0, pix=None):
     return Y, T
 
 
+def requantize(Y, fmt, scale):
+    """A layer's result as the next quantized layer's input codes (Section V: every convolution / linear input is
+    quantized): the fp32 value of each output through the activation quantizer of Eq. (6)-(9)."""
+    return quantize(np.asarray(Y, dtype=np.float64).astype(np.float32), fmt, scale)
+
+
+def requantize_bounds(Y, T, fmt, scale, rel, abs_):
+    """Codes of the lowest and highest fp32 values within the layer tolerance rel * T + abs_ of Y: the quantizer is
+    monotone, so a result inside the tolerance has a code whose value lies between theirs."""
+    Y = np.asarray(Y, dtype=np.float64)
+    tol = rel * np.asarray(T, dtype=np.float64) + abs_
+    lo = np.nextafter((Y - tol).astype(np.float32), np.float32(-np.inf))
+    hi = np.nextafter((Y + tol).astype(np.float32), np.float32(np.inf))
+    return quantize(lo, fmt, scale), quantize(hi, fmt, scale)
+
+
 def count_zeros(values):
     """Section VI, "Sparsity": the number of values of a tensor that are zero (+0 and -0 alike)."""
     return int(np.count_nonzero(np.asarray(values) == 0))

@@ -82,6 +82,11 @@ def lib():
     L.fpq_search_workspace_size.argtypes = [sz, i32, i32]
     L.fpq_search_format.restype = i32
     L.fpq_search_format.argtypes = [f32p, sz, vp, vp, i32, i32, f32p, vp, vp, sz, vp]
+    L.fpq_gemm_codes_out.restype = i32
+    L.fpq_gemm_codes_out.argtypes = [vp, i32, F, fl, f32p, vp, F, f32p, f32p, F, fl, f32p, u8p, i64, i64, i64, i32, vp, sz, vp]
+    L.fpq_conv2d_codes_out.restype = i32
+    L.fpq_conv2d_codes_out.argtypes = ([vp, i32, F, fl, f32p, vp, F, f32p, f32p, F, fl, f32p, u8p] + [i64] * 5 + [i32] * 5 +
+                                       [vp, sz, vp])
     L.fpq_count_zeros_workspace_size.restype = sz
     L.fpq_count_zeros_workspace_size.argtypes = [sz]
     L.fpq_count_zeros.restype = i32
@@ -94,7 +99,7 @@ EXPORTS = ["fpq_strerror", "fpq_format_max", "fpq_format_check", "fpq_bias_to_sc
            "fpq_absmax_workspace_size", "fpq_absmax", "fpq_quantize", "fpq_padded_channels", "fpq_quantize_nhwc",
            "fpq_dequantize", "fpq_packed_size", "fpq_pack_weights", "fpq_gemm_workspace_size", "fpq_gemm",
            "fpq_conv2d_workspace_size", "fpq_conv2d", "fpq_search_workspace_size", "fpq_search_format",
-           "fpq_count_zeros_workspace_size", "fpq_count_zeros"]
+           "fpq_count_zeros_workspace_size", "fpq_count_zeros", "fpq_gemm_codes_out", "fpq_conv2d_codes_out"]
 
 
 def fmt(f):
@@ -237,3 +242,20 @@ def fpq_conv2d(x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, y, B, Cin, 
     _check(lib().fpq_conv2d(_ptr(x), int(x_is_fp32), fmt(fx), float(sx), _ptr(sx_dev), _ptr(packed_w), fmt(fw), _ptr(sw),
                             _ptr(bias), _ptr(y), B, Cin, H, W, Cout, kh, kw, stride, pad, int(acc_mode),
                             _ptr(workspace), wb, _stream()), "fpq_conv2d")
+
+
+def fpq_gemm_codes_out(x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, fy, sy, sy_dev, yq, M, N, K,
+                       acc_mode=FPQ_ACC_FP32, workspace=None):
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().fpq_gemm_codes_out(_ptr(x), int(x_is_fp32), fmt(fx), float(sx), _ptr(sx_dev), _ptr(packed_w), fmt(fw),
+                                    _ptr(sw), _ptr(bias), fmt(fy), float(sy), _ptr(sy_dev), _ptr(yq), M, N, K,
+                                    int(acc_mode), _ptr(workspace), wb, _stream()), "fpq_gemm_codes_out")
+
+
+def fpq_conv2d_codes_out(x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, fy, sy, sy_dev, yq, B, Cin, H, W, Cout,
+                         kh, kw, stride, pad, acc_mode=FPQ_ACC_FP32, workspace=None):
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().fpq_conv2d_codes_out(_ptr(x), int(x_is_fp32), fmt(fx), float(sx), _ptr(sx_dev), _ptr(packed_w), fmt(fw),
+                                      _ptr(sw), _ptr(bias), fmt(fy), float(sy), _ptr(sy_dev), _ptr(yq), B, Cin, H, W,
+                                      Cout, kh, kw, stride, pad, int(acc_mode), _ptr(workspace), wb, _stream()),
+           "fpq_conv2d_codes_out")

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libfpq.so")
 OBJ = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "quant.hip", "search.hip", "sparsity.hip", "gemm.hip", "gemm_dma.hip"]
+SOURCES = ["api.hip", "quant.hip", "search.hip", "sparsity.hip", "gemm.hip", "gemm_dma.hip", "gemm_dma_q.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -30,7 +30,7 @@ def _compile(src):
 
 def build():
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=7) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", OUT])
     return OUT

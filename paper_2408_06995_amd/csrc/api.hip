@@ -331,7 +331,15 @@ size_t fpq_conv2d_workspace_size(int64_t B, int64_t Cin, int64_t H, int64_t W, i
            (x_is_fp32 == FPQ_X_FP32_DYNAMIC ? kDynScaleBytes : 0);
 }
 
-static int run_layer(const void* x, int x_is_fp32, fpq_format_t fx, float sx, const float* sx_dev,
+// Where a layer's result goes when it leaves as codes for the next quantized layer.
+struct CodesOut {
+    fpq_format_t f;
+    float s;
+    const float* s_dev;
+    uint8_t* yq;
+};
+
+static int run_layer(const CodesOut* out, const void* x, int x_is_fp32, fpq_format_t fx, float sx, const float* sx_dev,
                      const void* packed_w, fpq_format_t fw, const float* sw, const float* bias, float* y, int64_t B,
                      int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh, int kw, int stride, int pad,
                      int conv_out, int acc_mode, void* workspace, size_t workspace_bytes, void* stream)
@@ -356,12 +364,21 @@ static int run_layer(const void* x, int x_is_fp32, fpq_format_t fx, float sx, co
     if (M >= (int64_t)1 << 31 || B * H * W * Cp >= (int64_t)1 << 31 || M * Cout >= (int64_t)1 << 40 ||
         Cout >= (int64_t)1 << 24)
         return FPQ_ERR_SHAPE;
-    if (!x || !packed_w || !sw || !y) return FPQ_ERR_NULL;
+    if (!x || !packed_w || !sw || (out ? !out->yq : !y)) return FPQ_ERR_NULL;
+    QParams qy{0, 0, 0, 0.0f};
+    if (out) {
+        st = resolve_format(out->f, &qy);
+        if (st) return st;
+        if (is_four_bit(out->f)) return FPQ_ERR_UNSUPPORTED;   // codes out are the next layer's activations: one per byte
+        if (!out->s_dev && !scale_ok(out->s)) return FPQ_ERR_SCALE;
+        if (accumulate) return FPQ_ERR_UNSUPPORTED;
+        if (reinterpret_cast<uintptr_t>(out->yq) & 15) return FPQ_ERR_ALIGN;
+    }
     int xkind, wkind;
     float alpha;
     st = resolve_kinds(fx, qx.c, fw, qw.c, acc_mode, &xkind, &wkind, &alpha);
     if (st) return st;
-    if ((reinterpret_cast<uintptr_t>(packed_w) & 15) || (reinterpret_cast<uintptr_t>(y) & 3)) return FPQ_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(packed_w) & 15) || (!out && (reinterpret_cast<uintptr_t>(y) & 3))) return FPQ_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint8_t* xcodes;
     // workspace = [activation codes when the input is fp32][split-K partial results]; a caller that passes
@@ -429,6 +446,15 @@ static int run_layer(const void* x, int x_is_fp32, fpq_format_t fx, float sx, co
     a.we = fw.ebits; a.wm = fw.mbits; a.wb = fw.bias;
     a.acc_mode = acc_mode;
     a.accumulate = accumulate;
+    if (out) {
+        a.yq = out->yq;
+        a.ldq = (int)padded_channels(Cout);
+        a.ym = qy.m; a.yb = qy.b; a.yem = qy.em; a.yc = qy.c;
+        a.ykind = (out->f.ebits == 4 && out->f.mbits == 3 && out->f.bias == 7 && qy.c <= 448.0f) ? 1
+                  : (out->f.ebits == 5 && out->f.mbits == 2 && out->f.bias == 15 && qy.c <= 57344.0f) ? 2 : 0;
+        a.sy = out->s;
+        a.sy_dev = out->s_dev;
+    }
     a.partial = partial;
     a.splits = plan.splits;
     a.tile = plan.tile;
@@ -452,7 +478,7 @@ int fpq_gemm(const void* x, int x_is_fp32, fpq_format_t fx, float sx, const floa
 {
     if (M == 0 && N > 0 && K > 0) return FPQ_OK;
     if (M > 0 && M > 65535 && x_is_fp32 && padded_channels(K) != K) return FPQ_ERR_UNSUPPORTED;
-    return run_layer(x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, y, M, K, 1, 1, N, 1, 1, 1, 0, 0, acc_mode,
+    return run_layer(nullptr, x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, y, M, K, 1, 1, N, 1, 1, 1, 0, 0, acc_mode,
                      workspace, workspace_bytes, stream);
 }
 
@@ -461,8 +487,31 @@ int fpq_conv2d(const void* x, int x_is_fp32, fpq_format_t fx, float sx, const fl
                int64_t W, int64_t Cout, int kh, int kw, int stride, int pad, int acc_mode, void* workspace,
                size_t workspace_bytes, void* stream)
 {
-    return run_layer(x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, y, B, Cin, H, W, Cout, kh, kw, stride, pad,
+    return run_layer(nullptr, x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, y, B, Cin, H, W, Cout, kh, kw, stride, pad,
                      1, acc_mode, workspace, workspace_bytes, stream);
+}
+
+int fpq_gemm_codes_out(const void* x, int x_is_fp32, fpq_format_t fx, float sx, const float* sx_dev, const void* packed_w,
+                       fpq_format_t fw, const float* sw, const float* bias, fpq_format_t fy, float sy, const float* sy_dev,
+                       uint8_t* yq, int64_t M, int64_t N, int64_t K, int acc_mode, void* workspace, size_t workspace_bytes,
+                       void* stream)
+{
+    if (M == 0 && N > 0 && K > 0) return FPQ_OK;
+    if (M > 0 && M > 65535 && x_is_fp32 && padded_channels(K) != K) return FPQ_ERR_UNSUPPORTED;
+    const CodesOut out{fy, sy, sy_dev, yq};
+    return run_layer(&out, x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, nullptr, M, K, 1, 1, N, 1, 1, 1, 0, 0,
+                     acc_mode, workspace, workspace_bytes, stream);
+}
+
+int fpq_conv2d_codes_out(const void* x, int x_is_fp32, fpq_format_t fx, float sx, const float* sx_dev,
+                         const void* packed_w, fpq_format_t fw, const float* sw, const float* bias, fpq_format_t fy,
+                         float sy, const float* sy_dev, uint8_t* yq, int64_t B, int64_t Cin, int64_t H, int64_t W,
+                         int64_t Cout, int kh, int kw, int stride, int pad, int acc_mode, void* workspace,
+                         size_t workspace_bytes, void* stream)
+{
+    const CodesOut out{fy, sy, sy_dev, yq};
+    return run_layer(&out, x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, nullptr, B, Cin, H, W, Cout, kh, kw, stride,
+                     pad, 1, acc_mode, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -78,6 +78,16 @@ struct GemmArgs {
     int splits;             // number of K slices (>= 1)
     int tile;               // GemmTile chosen by plan_gemm
     int accumulate;         // 1: add the result to y instead of storing it
+    // Output as codes for the next quantized layer (not null): the fp32 result is quantized with Eq. (6)-(9)
+    // (format below, per-tensor scale sy / sy_dev) and written one code per byte, row-major [M, ldq]
+    // (a convolution's rows are its output pixels, i.e. channels-last); y is not written.
+    uint8_t* yq;
+    int ldq;                // codes per row: N rounded up to 16; columns N .. ldq - 1 receive code 0
+    int ym, yb, yem;        // output format: mantissa bits, bias, e + m
+    float yc;               // its max value
+    int ykind;              // 1 / 2: the format is the hardware's E4M3 / E5M2 (conversion instruction); 0: any other
+    float sy;               // host scale (used when sy_dev is null)
+    const float* sy_dev;
 };
 
 // Kernel family / tile for a problem, and how many K slices share an output tile.
@@ -190,5 +200,6 @@ int launch_pack_weights(const float* w, int64_t N, int64_t Cin, int taps, const 
 int launch_gemm(const GemmArgs& a, hipStream_t st);
 bool gemm_dma_applicable(const GemmArgs& a);
 int launch_gemm_dma(const GemmArgs& a, hipStream_t st);
+int launch_gemm_dma_q(const GemmArgs& a, hipStream_t st);   // the same with the result as codes (a.yq)
 
 }  // namespace fpq

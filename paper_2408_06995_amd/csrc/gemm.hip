@@ -327,6 +327,50 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a)
             }
         }
     };
+    if (a.yq) {
+        // codes out (row-major [M, ldq], one byte per output; columns N .. ldq - 1 get code 0)
+        const QParams qy{a.ym, a.yb, a.yem, a.yc};
+        const float ry = inv_scale(a.sy, a.sy_dev);
+        if (!CONV) {
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int n = n0 + wq * TQ + 32 * j + l32;
+                if (n >= a.ldq) continue;
+                const float sc = n < a.N ? sxa * a.sw[n] : 0.0f;
+                const float bv = (n < a.N && a.bias) ? a.bias[n] : 0.0f;
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int m = m0 + wp * TP + 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
+                        if (m < a.M)
+                            a.yq[(size_t)m * a.ldq + n] =
+                                n < a.N ? (uint8_t)quantize_nearest(acc[i][j][r] * sc + bv, ry, qy) : (uint8_t)0;
+                    }
+            }
+        } else {
+            // P = weights: a lane is a pixel m, its registers run over channels n (4 consecutive ones per r / 4)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int m = m0 + wq * TQ + 32 * j + l32;
+                if (m >= a.M) continue;
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int n = n0 + wp * TP + 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
+                        if (n < a.N) {
+                            const float sc = sxa * a.sw[n];
+                            const float bv = a.bias ? a.bias[n] : 0.0f;
+                            a.yq[(size_t)m * a.ldq + n] = (uint8_t)quantize_nearest(acc[i][j][r] * sc + bv, ry, qy);
+                        } else if (n < a.ldq) {
+                            a.yq[(size_t)m * a.ldq + n] = 0;
+                        }
+                    }
+            }
+        }
+        return;
+    }
     if (a.accumulate)
         store_all(std::true_type{});
     else
