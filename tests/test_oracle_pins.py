@@ -587,3 +587,56 @@ def test_sparsity_of_quantized_gaussian_equals_closed_form(fmt):
     assert abs(got - p) < 5 * math.sqrt(p * (1 - p) / n) + 1e-6
     # the quantized tensor is far sparser than the fp32 one it came from (no exact zeros there)
     assert oracle.count_zeros(x) == 0 and got > 0
+
+
+# ---- a layer's result as the next layer's codes (Section V: every conv / linear input is quantized)
+
+
+def test_requantize_is_the_quantizer_on_the_fp32_result():
+    """Brute force: each double result rounded to fp32, multiplied by fl32(1 / scale) in fp32, then the nearest grid
+    value found by search over the grid enumerated from Eq. (5)."""
+    rng = np.random.default_rng(5)
+    e, m, b, c = synth.E4M3
+    Y = rng.normal(0, 3.0, 4000) * (1 + 1e-9)                   # doubles that are not fp32 values
+    scale = np.float32(0.0123)
+    got = oracle.requantize(Y, synth.E4M3, float(scale))
+    r = np.float32(1.0) / scale
+    for yi, ci in zip(Y.tolist(), got.tolist()):
+        y32 = float(np.float32(np.float32(yi) * r))
+        assert ci == brute_nearest_code(y32, e, m, b, c)
+
+
+def test_identity_layer_reproduces_its_input_codes():
+    """Weights = identity with scale 1, output format and scale = input format and scale: the layer's result is the
+    dequantized input, so quantizing it again gives back the input codes."""
+    rng = np.random.default_rng(11)
+    for f in (synth.E4M3, synth.E3M4, synth.E5M2):
+        e, m = f[0], f[1]
+        N = 24
+        xq = rng.integers(0, 1 << (1 + e + m), size=(40, N), dtype=np.uint8)
+        ok = oracle.dequantize(xq, f)
+        xq[np.abs(ok) > f[3]] = 1                                 # codes beyond the format's max value are not its codes
+        xq[xq == (1 << (e + m))] = 0                              # a sum of zeros of both signs is +0
+        wq, sw = oracle.pack_weights(np.eye(N, dtype=np.float32), f, None, np.ones(N, dtype=np.float32))
+        Y, T = oracle.gemm(xq, f, 0.037, wq, f, sw)
+        assert np.array_equal(oracle.requantize(Y, f, 0.037), xq)
+
+
+def test_requantize_bounds_bracket_the_result_and_close_up_away_from_boundaries():
+    rng = np.random.default_rng(13)
+    f = synth.E4M3
+    g = np.array(eq5_grid(f[0], f[1], f[2]))
+    g = g[g <= f[3]]
+    mids = (g[:-1] + g[1:]) / 2
+    centres = g[5:-5]
+    Y = np.concatenate([centres, -centres, mids[5:-5] * (1 + 1e-7)])       # grid values, and points just past a midpoint
+    T = np.abs(Y) * 3
+    lo, hi = oracle.requantize_bounds(Y, T, f, 1.0, 1e-5, 1e-9)
+    mid = oracle.requantize(Y, f, 1.0)
+    vlo, vmid, vhi = (oracle.dequantize(c, f) for c in (lo, mid, hi))
+    assert np.all(vlo <= vmid) and np.all(vmid <= vhi)
+    n = 2 * centres.size
+    assert np.array_equal(lo[:n], hi[:n]) and np.array_equal(lo[:n], mid[:n])   # decided: far from any boundary
+    assert np.all(lo[n:] != hi[n:])                                             # undecided: the tolerance spans the midpoint
+    # the two bounds are neighbours on the grid there
+    assert np.all(np.abs(np.searchsorted(g, vhi[n:]) - np.searchsorted(g, vlo[n:])) == 1)
