@@ -338,6 +338,25 @@ def main():
                     e1.synchronize()
                     us = e0.elapsed_time(e1) * 1e3 / 64
                     entry["%s_%s" % (tag, mname)] = {"us": round(us, 2), "TFLOP/s": round(synth.flops(L) / us / 1e6, 1)}
+                if L.kind == "linear":
+                    # the feed-forward projection as the U-Net runs it: gated GELU between the result and its codes
+                    def gated():
+                        B.fpq_gemm_codes_out(cb, 0, FX, 0.0, st2[1:2], pk, fw, sw, None, FX, 0.05, None, yq, L.M, L.N, L.K,
+                                             B.FPQ_ACC_FP32 | B.FPQ_ACT_GEGLU, wsb)
+                    gated()
+                    torch.cuda.synchronize()
+                    g3 = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g3):
+                        for _ in range(16):
+                            gated()
+                    g3.replay()
+                    e0.record()
+                    for _ in range(4):
+                        g3.replay()
+                    e1.record()
+                    e1.synchronize()
+                    us = e0.elapsed_time(e1) * 1e3 / 64
+                    entry["%s_fp32_geglu_codes_out" % tag] = {"us": round(us, 2), "TFLOP/s": round(synth.flops(L) / us / 1e6, 1)}
                 if L.kind == "linear" and tag == "w8a8":
                     # what the codes-out form replaces when the next layer is quantized too: the fp32 result written,
                     # then read again by the next layer's quantize pass (static scale)

@@ -71,6 +71,8 @@ typedef enum fpq_acc_mode { FPQ_ACC_FP32 = 0, FPQ_ACC_FP8_MFMA = 1 } fpq_acc_mod
  * and the previous layer's output have different value distributions), is then one call per part on that
  * part's codes and that part's slice of the weights, the second and later calls with this flag. */
 #define FPQ_OUT_ACCUMULATE 0x100
+#define FPQ_ACT_SILU 0x200  /* codes-out entry points only, see there */
+#define FPQ_ACT_GEGLU 0x400
 
 /* What the x argument of fpq_gemm / fpq_conv2d holds (their x_is_fp32 argument).
  * FPQ_X_CODES: codes written by fpq_quantize / fpq_quantize_nhwc with scale sx.
@@ -237,7 +239,19 @@ int fpq_conv2d(const void *x, int x_is_fp32, fpq_format_t fx, float sx, const fl
  * 16-byte aligned.  For a convolution the rows are the output pixels in (b, ho, wo) order, i.e. the
  * channels-last buffer [B, Ho, Wo, Np] that fpq_conv2d takes as codes; for a linear layer with
  * N % 16 == 0 it is the [M, K = N] code matrix that fpq_gemm takes.  All other arguments, the workspace
- * and its size are those of fpq_gemm / fpq_conv2d; FPQ_OUT_ACCUMULATE is not accepted.  Because v
+ * and its size are those of fpq_gemm / fpq_conv2d; FPQ_OUT_ACCUMULATE is not accepted.
+ *
+ * An activation can stand between the result and its codes (the U-Net has one between the two linear
+ * layers of every feed-forward block), OR-ed into acc_mode:
+ *   FPQ_ACT_SILU   yq = Q(v * sigmoid(v));
+ *   FPQ_ACT_GEGLU  (fpq_gemm_codes_out only, N % 32 == 0) the columns of v come in blocks of 32, the
+ *                  first 16 of a block values a, the last 16 gates g of the same 16 outputs:
+ *                  yq[m, 16 B + i] = Q(v[m, 32 B + i] * gelu(v[m, 32 B + 16 + i])) with
+ *                  gelu(g) = g * Phi(g) (the exact, erf-based form); yq is [M, N / 2].  A caller
+ *                  whose projection holds all values before all gates reorders the weight rows,
+ *                  scales and biases once, before fpq_pack_weights.
+ * The activation is evaluated in fp32: sigmoid to a relative error below 1e-6, gelu(g) to an absolute
+ * error below 4e-7 |g| (erf by a five-term rational approximation).  Because v
  * depends on the summation order within the fp32 tolerance, a code can differ from the one computed
  * from an exactly rounded v where v lies within that tolerance of a rounding boundary of fy. */
 int fpq_gemm_codes_out(const void *x, int x_is_fp32, fpq_format_t fx, float sx, const float *sx_dev,

@@ -212,6 +212,28 @@ def conv2d(xq, fx, sx, wq, fw, sw, bias=None, stride=1, pad=0, pix=None):
     return Y, T
 
 
+def silu(v):
+    """v * sigmoid(v) in double."""
+    v = np.asarray(v, dtype=np.float64)
+    return v / (1.0 + np.exp(-v))
+
+
+def gelu(g):
+    """g * Phi(g), Phi the standard normal distribution function (the exact, erf-based form), in double."""
+    from scipy.special import erfc
+    g = np.asarray(g, dtype=np.float64)
+    return 0.5 * g * erfc(-g / np.sqrt(2.0))
+
+
+def geglu(V):
+    """Gated GELU on a layer result whose columns come in blocks of 32, the first 16 of a block values, the last 16
+    the gates of the same outputs: [M, N] -> [M, N / 2]."""
+    V = np.asarray(V, dtype=np.float64)
+    M, N = V.shape
+    blocks = V.reshape(M, N // 32, 2, 16)
+    return (blocks[:, :, 0, :] * gelu(blocks[:, :, 1, :])).reshape(M, N // 2)
+
+
 def requantize(Y, fmt, scale):
     """A layer's result as the next quantized layer's input codes (Section V: every convolution / linear input is
     quantized): the fp32 value of each output through the activation quantizer of Eq. (6)-(9)."""

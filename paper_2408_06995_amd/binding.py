@@ -14,6 +14,8 @@ LIB_PATH = os.environ.get("FPQ_LIB_PATH") or os.path.join(HERE, "libfpq.so")   #
 FPQ_ACC_FP32 = 0
 FPQ_ACC_FP8_MFMA = 1
 FPQ_OUT_ACCUMULATE = 0x100
+FPQ_ACT_SILU = 0x200
+FPQ_ACT_GEGLU = 0x400
 FPQ_X_CODES = 0
 FPQ_X_FP32 = 1
 FPQ_X_FP32_DYNAMIC = 2

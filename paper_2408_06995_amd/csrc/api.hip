@@ -345,7 +345,11 @@ static int run_layer(const CodesOut* out, const void* x, int x_is_fp32, fpq_form
                      int conv_out, int acc_mode, void* workspace, size_t workspace_bytes, void* stream)
 {
     const int accumulate = (acc_mode & FPQ_OUT_ACCUMULATE) ? 1 : 0;
-    acc_mode &= ~FPQ_OUT_ACCUMULATE;
+    const int act = acc_mode & (FPQ_ACT_SILU | FPQ_ACT_GEGLU);
+    acc_mode &= ~(FPQ_OUT_ACCUMULATE | FPQ_ACT_SILU | FPQ_ACT_GEGLU);
+    if (act && !out) return FPQ_ERR_UNSUPPORTED;                       // activations exist in the codes-out form only
+    if (act == (FPQ_ACT_SILU | FPQ_ACT_GEGLU)) return FPQ_ERR_UNSUPPORTED;
+    if (act == FPQ_ACT_GEGLU && (conv_out || Cout % 32 != 0)) return FPQ_ERR_UNSUPPORTED;
     QParams qx, qw;
     int st = resolve_format(fx, &qx);
     if (st) return st;
@@ -448,7 +452,8 @@ static int run_layer(const CodesOut* out, const void* x, int x_is_fp32, fpq_form
     a.accumulate = accumulate;
     if (out) {
         a.yq = out->yq;
-        a.ldq = (int)padded_channels(Cout);
+        a.act = act;
+        a.ldq = (int)(act == FPQ_ACT_GEGLU ? Cout / 2 : padded_channels(Cout));
         a.ym = qy.m; a.yb = qy.b; a.yem = qy.em; a.yc = qy.c;
         a.ykind = (out->f.ebits == 4 && out->f.mbits == 3 && out->f.bias == 7 && qy.c <= 448.0f) ? 1
                   : (out->f.ebits == 5 && out->f.mbits == 2 && out->f.bias == 15 && qy.c <= 57344.0f) ? 2 : 0;

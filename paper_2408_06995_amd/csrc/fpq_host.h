@@ -88,6 +88,7 @@ struct GemmArgs {
     int ykind;              // 1 / 2: the format is the hardware's E4M3 / E5M2 (conversion instruction); 0: any other
     float sy;               // host scale (used when sy_dev is null)
     const float* sy_dev;
+    int act;                // 0, FPQ_ACT_SILU or FPQ_ACT_GEGLU: applied to the fp32 result before it is quantized
 };
 
 // Kernel family / tile for a problem, and how many K slices share an output tile.

@@ -334,8 +334,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a)
         if (!CONV) {
 #pragma unroll
             for (int j = 0; j < NI; ++j) {
-                const int n = n0 + wq * TQ + 32 * j + l32;
-                if (n >= a.ldq) continue;
+                const int n = n0 + wq * TQ + 32 * j + l32;    // tiles start at multiples of 32: a block of 32 columns is one j
                 const float sc = n < a.N ? sxa * a.sw[n] : 0.0f;
                 const float bv = (n < a.N && a.bias) ? a.bias[n] : 0.0f;
 #pragma unroll
@@ -343,9 +342,17 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int m = m0 + wp * TP + 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
-                        if (m < a.M)
-                            a.yq[(size_t)m * a.ldq + n] =
-                                n < a.N ? (uint8_t)quantize_nearest(acc[i][j][r] * sc + bv, ry, qy) : (uint8_t)0;
+                        float v = acc[i][j][r] * sc + bv;
+                        if (a.act == FPQ_ACT_GEGLU) {
+                            // lanes 0-15 of each 32: values, lanes 16-31: the gates of the same outputs (all lanes exchange)
+                            v *= act_gelu_call(lane_xor16(v));
+                            if (m < a.M && l32 < 16 && n < a.N)
+                                a.yq[(size_t)m * a.ldq + ((n - l32) >> 1) + l32] = (uint8_t)quantize_nearest(v, ry, qy);
+                        } else {
+                            if (a.act == FPQ_ACT_SILU) v = act_silu_call(v);
+                            if (m < a.M && n < a.ldq)
+                                a.yq[(size_t)m * a.ldq + n] = n < a.N ? (uint8_t)quantize_nearest(v, ry, qy) : (uint8_t)0;
+                        }
                     }
             }
         } else {
@@ -362,7 +369,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a)
                         if (n < a.N) {
                             const float sc = sxa * a.sw[n];
                             const float bv = a.bias ? a.bias[n] : 0.0f;
-                            a.yq[(size_t)m * a.ldq + n] = (uint8_t)quantize_nearest(acc[i][j][r] * sc + bv, ry, qy);
+                            float v = acc[i][j][r] * sc + bv;
+                            if (a.act == FPQ_ACT_SILU) v = act_silu_call(v);
+                            a.yq[(size_t)m * a.ldq + n] = (uint8_t)quantize_nearest(v, ry, qy);
                         } else if (n < a.ldq) {
                             a.yq[(size_t)m * a.ldq + n] = 0;
                         }

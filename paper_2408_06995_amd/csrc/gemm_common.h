@@ -11,6 +11,39 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 
+// ---------------------------------------------------------------------------------- activations (codes out)
+
+// x * sigmoid(x) with the hardware exponential and reciprocal: relative error below 1e-6.  For very negative x the
+// exponential overflows to +inf and the product is -0: the exact value is below the smallest fp32 number there.
+__device__ __forceinline__ float act_silu(float x) { return x * __frcp_rn(1.0f + __expf(-x)); }
+
+// g * Phi(g), Phi the standard normal distribution function = 1 - erfc(g / sqrt 2) / 2, with
+// erfc(z) = t (a1 + t (a2 + t (a3 + t (a4 + t a5)))) exp(-z^2), t = 1 / (1 + p z), z >= 0 (Abramowitz & Stegun
+// 7.1.26, absolute error of the formula 1.5e-7); the negative side uses Phi(g) = erfc(|g| / sqrt 2) / 2 directly, so
+// nothing cancels.  Absolute error of the result below 4e-7 |g|.
+__device__ __forceinline__ float act_gelu(float g)
+{
+    const float z = fabsf(g) * 0.70710678118654752f;
+    const float t = __frcp_rn(fmaf(0.3275911f, z, 1.0f));
+    float p = fmaf(t, 1.061405429f, -1.453152027f);
+    p = fmaf(t, p, 1.421413741f);
+    p = fmaf(t, p, -0.284496736f);
+    p = fmaf(t, p, 0.254829592f);
+    const float half_erfc = 0.5f * t * p * __expf(-z * z);     // Phi(-|g|)
+    return g * (g < 0.0f ? half_erfc : 1.0f - half_erfc);
+}
+
+// The same as real function calls, for the rarely taken, fully unrolled element-wise paths (edge tiles, the
+// register-staged kernels), where inlining them a few hundred times over makes the kernels spill.
+__device__ __attribute__((noinline)) float act_silu_call(float x) { return act_silu(x); }
+__device__ __attribute__((noinline)) float act_gelu_call(float g) { return act_gelu(g); }
+
+// The value of the lane 16 away inside each group of 32 lanes (ds_swizzle, bit-mask mode: xor 0x10).
+__device__ __forceinline__ float lane_xor16(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));
+}
+
 // ---------------------------------------------------------------------------------- LDS geometry
 
 // Byte offset of 16-byte chunk c of a tile row.  Rows are ROWB (128 or 64) bytes; the chunk index

@@ -36,7 +36,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 // Codes out with split-K: the row-major partial sums [splits][M, N] are added in slice order, quantized and written
 // as codes [M, ldq]; a thread takes four consecutive columns of a row (one 32-bit store), columns N .. ldq - 1 get 0.
 __global__ __launch_bounds__(256) void splitk_reduce_codes_kernel(const float* __restrict__ partial, int M, int N, int ldq,
-                                                                  int splits, QParams qy, float sy,
+                                                                  int splits, int act, QParams qy, float sy,
                                                                   const float* __restrict__ sy_dev,
                                                                   uint8_t* __restrict__ yq)
 {
@@ -44,34 +44,56 @@ __global__ __launch_bounds__(256) void splitk_reduce_codes_kernel(const float* _
     const size_t slice = (size_t)M * N;
     const int groups = ldq >> 2;
     const size_t total = (size_t)M * groups;
-    for (size_t t = (size_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (size_t)gridDim.x * 256) {
-        const int m = (int)(t / groups);
-        const int n = (int)(t - (size_t)m * groups) * 4;
-        uint32_t word = 0;
-        if ((N & 3) == 0 && n + 3 < N) {   // the partial sums are 256-byte aligned: rows of 4 k floats keep 16-byte groups aligned
+    // sum over the slices of four consecutive columns of row m starting at column n (n % 4 == 0, inside the row)
+    auto sum4 = [&](int m, int n, float (&v)[4]) {
+        if ((N & 3) == 0 && n + 3 < N) {   // partial sums are 256-byte aligned: rows of 4 k floats keep 16-byte groups aligned
             const size_t idx = (size_t)m * N + n;
-            float4 v = *reinterpret_cast<const float4*>(partial + idx);
+            float4 t = *reinterpret_cast<const float4*>(partial + idx);
             for (int s = 1; s < splits; ++s) {
                 const float4 p = *reinterpret_cast<const float4*>(partial + (size_t)s * slice + idx);
-                v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+                t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
             }
-            word = quantize_nearest(v.x, ry, qy) | (quantize_nearest(v.y, ry, qy) << 8) |
-                   (quantize_nearest(v.z, ry, qy) << 16) | (quantize_nearest(v.w, ry, qy) << 24);
+            v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
         } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
+                v[e] = 0.0f;
                 if (n + e < N) {
                     const size_t idx = (size_t)m * N + n + e;
-                    float v = partial[idx];
-                    for (int s = 1; s < splits; ++s) v += partial[(size_t)s * slice + idx];
-                    word |= quantize_nearest(v, ry, qy) << (8 * e);
+                    v[e] = partial[idx];
+                    for (int s = 1; s < splits; ++s) v[e] += partial[(size_t)s * slice + idx];
                 }
             }
         }
+    };
+    for (size_t t = (size_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (size_t)gridDim.x * 256) {
+        const int m = (int)(t / groups);
+        const int n = (int)(t - (size_t)m * groups) * 4;      // output column
+        float v[4];
+        int valid = 4;
+        if (act == FPQ_ACT_GEGLU) {
+            // outputs n .. n + 3 of block n / 16: values at columns 32 (n / 16) + n % 16, gates 16 further on
+            const int col = 32 * (n >> 4) + (n & 15);
+            float gate[4];
+            sum4(m, col, v);
+            sum4(m, col + 16, gate);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] *= act_gelu(gate[e]);
+        } else {
+            sum4(m, n, v);
+            valid = N - n < 4 ? (N - n > 0 ? N - n : 0) : 4;
+            if (act == FPQ_ACT_SILU) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = act_silu(v[e]);
+            }
+        }
+        uint32_t word = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (e < valid) word |= quantize_nearest(v[e], ry, qy) << (8 * e);
         *reinterpret_cast<uint32_t*>(yq + (size_t)m * ldq + n) = word;
     }
 }
-
 
 int launch_splitk_reduce(const GemmArgs& a, hipStream_t st)
 {
@@ -80,7 +102,7 @@ int launch_splitk_reduce(const GemmArgs& a, hipStream_t st)
         size_t grid = ((size_t)a.M * (a.ldq / 4) + 255) / 256;
         if (grid > 4096) grid = 4096;
         hipLaunchKernelGGL(splitk_reduce_codes_kernel, dim3((unsigned)grid), dim3(256), 0, st, a.partial, a.M, a.N, a.ldq,
-                           a.splits, qy, a.sy, a.sy_dev, a.yq);
+                           a.splits, a.act, qy, a.sy, a.sy_dev, a.yq);
     } else {
         const size_t n = (size_t)a.M * a.N;
         size_t grid = (n / 4 + 255) / 256;

@@ -41,7 +41,7 @@ __device__ __forceinline__ void dma16(v4i rsrc, unsigned voff, unsigned lds_addr
 {
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :
-                 : "s"(lds_addr), "v"(voff), "s"(rsrc)
+                 : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(rsrc)   // uniform, but may live in a VGPR
                  : "memory");
 }
 
@@ -528,7 +528,7 @@ __global__ __launch_bounds__(256, ((BX <= 128 && NSTAGE <= 2) ? 2 : 1)) void gem
             // codes of its column (one word), then a 4 x 4 byte transpose inside each quad of lanes leaves lane
             // (a, b) with row 8 q + 4 g + b, columns 4 a .. 4 a + 3 of the column block: one 32-bit store, and
             // eight lanes cover 32 consecutive bytes of a row.
-            if (full) {
+            if (full && (a.ykind != 0 || a.act == 0)) {
                 uint32_t sel1, sel2;
                 transpose_selectors(qb, sel1, sel2);
                 float sc[NI], bv[NI];
@@ -539,9 +539,12 @@ __global__ __launch_bounds__(256, ((BX <= 128 && NSTAGE <= 2) ? 2 : 1)) void gem
                 }
                 // the column blocks innermost: the five 32-byte pieces of a row's 160 bytes leave back to back.
                 // One copy of the loops per conversion kind, chosen once per tile.
-                auto codes_tile = [&](auto kind) {
+                auto codes_tile = [&](auto kind, auto activation) {
                     constexpr int YK = decltype(kind)::value;
-                    uint8_t* rowp = a.yq + (size_t)(mw + 4 * g + qb) * a.ldq + n0 + 4 * qa;
+                    constexpr int ACT = decltype(activation)::value;
+                    // GEGLU halves the row: block j's 16 outputs sit at columns (n0 + 32 j) / 2 .. + 15
+                    uint8_t* rowp = ACT == FPQ_ACT_GEGLU ? a.yq + (size_t)(mw + 4 * g + qb) * a.ldq + (n0 >> 1) + 4 * qa
+                                                         : a.yq + (size_t)(mw + 4 * g + qb) * a.ldq + n0 + 4 * qa;
                     const size_t step = (size_t)8 * a.ldq;
 #pragma unroll
                     for (int i = 0; i < MI; ++i)
@@ -549,37 +552,78 @@ __global__ __launch_bounds__(256, ((BX <= 128 && NSTAGE <= 2) ? 2 : 1)) void gem
                         for (int q4 = 0; q4 < 4; ++q4) {
 #pragma unroll
                             for (int j = 0; j < NI; ++j) {
-                                const uint32_t col = codes_of4<YK>(
-                                    acc[i][j][4 * q4] * sc[j] + bv[j], acc[i][j][4 * q4 + 1] * sc[j] + bv[j],
-                                    acc[i][j][4 * q4 + 2] * sc[j] + bv[j], acc[i][j][4 * q4 + 3] * sc[j] + bv[j], ry, qy);
-                                __builtin_nontemporal_store(quad_transpose_bytes(col, sel1, sel2),
-                                                            reinterpret_cast<uint32_t*>(rowp + 32 * j));
+                                float v[4];
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q4 + e] * sc[j] + bv[j];
+                                if (ACT == FPQ_ACT_SILU) {
+#pragma unroll
+                                    for (int e = 0; e < 4; ++e) v[e] = act_silu(v[e]);
+                                }
+                                if (ACT == FPQ_ACT_GEGLU) {
+                                    // lanes 0-15 of each 32 hold the values, lanes 16-31 the gates of the same outputs.
+                                    // One gelu serves two rows: the value lanes take the partner's gate of row e, the
+                                    // gate lanes keep their own gate of row e + 1 and send the result back afterwards.
+#pragma unroll
+                                    for (int e = 0; e < 4; e += 2) {
+                                        const float partner = lane_xor16(v[e]);      // every lane takes part
+                                        const float ge = act_gelu(l32 < 16 ? partner : v[e + 1]);
+                                        const float back = lane_xor16(ge);
+                                        v[e] *= ge;            // meaningful in the value lanes only
+                                        v[e + 1] *= back;
+                                    }
+                                }
+                                const uint32_t row = quad_transpose_bytes(codes_of4<YK>(v[0], v[1], v[2], v[3], ry, qy), sel1, sel2);
+                                if (ACT == FPQ_ACT_GEGLU) {
+                                    if (l32 < 16) __builtin_nontemporal_store(row, reinterpret_cast<uint32_t*>(rowp + 16 * j));
+                                } else {
+                                    __builtin_nontemporal_store(row, reinterpret_cast<uint32_t*>(rowp + 32 * j));
+                                }
                             }
                             rowp += step;
                         }
                 };
-                if (a.ykind == 1)
-                    codes_tile(std::integral_constant<int, 1>{});
-                else if (a.ykind == 2)
-                    codes_tile(std::integral_constant<int, 2>{});
-                else
-                    codes_tile(std::integral_constant<int, 0>{});
+                // the hardware formats get a copy per activation; the arithmetic encoder (rare as an output format,
+                // and large) only the plain one, its activations go through the element-wise path below
+                if (a.ykind == 1) {
+                    if (a.act == FPQ_ACT_GEGLU)
+                        codes_tile(std::integral_constant<int, 1>{}, std::integral_constant<int, FPQ_ACT_GEGLU>{});
+                    else if (a.act == FPQ_ACT_SILU)
+                        codes_tile(std::integral_constant<int, 1>{}, std::integral_constant<int, FPQ_ACT_SILU>{});
+                    else
+                        codes_tile(std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{});
+                } else if (a.ykind == 2) {
+                    if (a.act == FPQ_ACT_GEGLU)
+                        codes_tile(std::integral_constant<int, 2>{}, std::integral_constant<int, FPQ_ACT_GEGLU>{});
+                    else if (a.act == FPQ_ACT_SILU)
+                        codes_tile(std::integral_constant<int, 2>{}, std::integral_constant<int, FPQ_ACT_SILU>{});
+                    else
+                        codes_tile(std::integral_constant<int, 2>{}, std::integral_constant<int, 0>{});
+                } else {
+                    codes_tile(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+                }
                 return W_AFTER_CODES;
             }
             // tiles that cross the edge of the output: byte stores; the padding columns N .. ldq - 1 get code 0
 #pragma unroll
             for (int j = 0; j < NI; ++j) {
                 const int n = n0 + 32 * j + l32;
-                const float sc = sxa * stab[32 * j + l32];
-                const float bv = stab[256 + 32 * j + l32];
+                const float sc1 = sxa * stab[32 * j + l32];
+                const float bv1 = stab[256 + 32 * j + l32];
 #pragma unroll
                 for (int i = 0; i < MI; ++i)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int m = mw + 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
-                        if (m < a.M && n < a.ldq)
-                            a.yq[(size_t)m * a.ldq + n] =
-                                n < a.N ? (uint8_t)quantize_nearest(acc[i][j][r] * sc + bv, ry, qy) : (uint8_t)0;
+                        float v = acc[i][j][r] * sc1 + bv1;
+                        if (a.act == FPQ_ACT_GEGLU) {
+                            v *= act_gelu_call(lane_xor16(v));      // every lane takes part in the exchange
+                            const int no = ((n0 + 32 * j) >> 1) + l32;
+                            if (m < a.M && l32 < 16 && n < a.N) a.yq[(size_t)m * a.ldq + no] = (uint8_t)quantize_nearest(v, ry, qy);
+                        } else {
+                            if (a.act == FPQ_ACT_SILU) v = act_silu_call(v);
+                            if (m < a.M && n < a.ldq)
+                                a.yq[(size_t)m * a.ldq + n] = n < a.N ? (uint8_t)quantize_nearest(v, ry, qy) : (uint8_t)0;
+                        }
                     }
             }
             return W_DRAIN;

@@ -124,6 +124,98 @@ def test_epilogue_quantizer_bit_exact_on_single_term_sums(M, N, fy, ratio):
     assert len(np.unique(want)) > 4
 
 
+def check_codes_interval(got, O, tol, fy, sy, what):
+    """got: uint8 [M, No]; O: exact result of the whole epilogue (double), tol: its error bound per element."""
+    lo = oracle.quantize(np.nextafter((O - tol).astype(np.float32), np.float32(-np.inf)), fy, sy)
+    hi = oracle.quantize(np.nextafter((O + tol).astype(np.float32), np.float32(np.inf)), fy, sy)
+    vlo, vhi, vg = (oracle.dequantize(c, fy) for c in (lo, hi, got))
+    bad = (vg < vlo) | (vg > vhi)
+    assert not bad.any(), "%s: %d of %d codes outside the tolerance interval" % (what, int(bad.sum()), bad.size)
+    same = lo == hi
+    assert np.array_equal(got[same], lo[same]), what
+    return float((got != oracle.requantize(O, fy, sy)).mean())
+
+
+# generic kernel, 128-row tile (whole and ragged), split K, 256-row tile; N % 32 == 0 for the gated form
+ACT_SHAPES = [(77, 768, 320), (130, 128, 64), (8192, 320, 320), (8200, 320, 640), (300, 2880, 320), (24576, 2048, 320)]
+
+
+@pytest.mark.parametrize("M,K,N", ACT_SHAPES)
+@pytest.mark.parametrize("fw,fy,acc", [(E4M3, E4M3, 0), (E2M1, E3M4, 0), (E2M1, E4M3, 1)])
+@pytest.mark.parametrize("act", ["silu", "geglu"])
+def test_linear_activation_then_codes(M, K, N, fw, fy, acc, act):
+    fx = E4M3
+    x = synth.activations((M, K), 7000 + M)
+    w = synth.weights((N, K), 7500 + N) * 4.0          # results of order 1, where the activations bend
+    h = synth.rounding_mask((N, K), 7750 + N) if fw is E2M1 else None
+    bias = np.linspace(-1, 1, N).astype(np.float32)
+    sx, xq, wq, sw = oracle_linear_inputs(x, w, h, fx, fw)
+    Y, T = oracle.gemm(xq, fx, sx, wq, fw, sw, bias)
+    t = (REL_FP8_MFMA if acc else 1e-5) * T + 1e-6
+    if act == "silu":
+        O = oracle.silu(Y)
+        tol = 1.1 * t + 1e-6 * np.abs(O) + 1e-12        # |silu'| <= 1.1; fp32 evaluation of the activation
+        flag, No = B.FPQ_ACT_SILU, N
+    else:
+        O = oracle.geglu(Y)
+        Yb, tb = Y.reshape(M, N // 32, 2, 16), t.reshape(M, N // 32, 2, 16)
+        a, g, ta, tg = Yb[:, :, 0, :], Yb[:, :, 1, :], tb[:, :, 0, :], tb[:, :, 1, :]
+        G = oracle.gelu(g)
+        dG = 1.13 * tg + 4e-7 * np.abs(g) + 1e-6 * np.abs(G) + 1e-12      # |gelu'| <= 1.13; the kernel's erf approximation
+        tol = (np.abs(G) * ta + (np.abs(a) + ta) * dG + 1e-6 * np.abs(a * G)).reshape(M, N // 2)
+        flag, No = B.FPQ_ACT_GEGLU, N // 2
+    sy = out_scale(O, fy)
+    packed, sw_t, _ = gpu_pack(w, fw, h, want_codes=False)
+    Np = B.fpq_padded_channels(No)
+    buf = torch.full((M * Np + 32,), 0xEE, dtype=torch.uint8, device=DEV)
+    ws = torch.empty(max(256, B.fpq_gemm_workspace_size(M, N, K, 0)), dtype=torch.uint8, device=DEV)
+    B.fpq_gemm_codes_out(dev(xq), 0, fx, sx, None, packed, fw, sw_t, dev(bias), fy, sy, None, buf[16:], M, N, K, acc | flag, ws)
+    torch.cuda.synchronize()
+    hb = buf.cpu().numpy()
+    assert np.all(hb[:16] == 0xEE) and np.all(hb[16 + M * Np:] == 0xEE), "written outside the code matrix"
+    got = hb[16:16 + M * Np].reshape(M, Np)
+    assert np.all(got[:, No:] == 0)
+    miss = check_codes_interval(got[:, :No], O, tol, fy, sy, "%s then codes %s" % (act, (M, K, N, fw, fy, acc)))
+    if not acc:
+        assert miss < 0.005
+
+
+@pytest.mark.parametrize("case", [(2, 32, 5, 5, 64, 1, 1, 0), (1, 48, 12, 10, 130, 3, 1, 0), (2, 64, 65, 63, 160, 3, 2, 1),
+                                  (1, 640, 16, 16, 160, 3, 1, 1)])
+def test_conv_silu_then_codes(case):
+    Bn, Cin, H, W, Cout, k, stride, pad = case
+    fx = fw = fy = E4M3
+    x = synth.activations((Bn, Cin, H, W), 8000 + Cin)
+    w = synth.weights((Cout, Cin, k, k), 8500 + Cout) * 4.0
+    bias = np.linspace(-0.5, 0.5, Cout).astype(np.float32)
+    sx = oracle.scale_from_absmax(oracle.absmax(x), fx[3])
+    xq = oracle.quantize(x, fx, sx)
+    wq, sw = oracle.pack_weights(w, fw, None)
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    M = Bn * Ho * Wo
+    Y, T = oracle.conv2d(xq, fx, sx, wq, fw, sw, bias, stride=stride, pad=pad)
+    Y = Y.transpose(0, 2, 3, 1).reshape(M, Cout)
+    T = T.transpose(0, 2, 3, 1).reshape(M, Cout)
+    O = oracle.silu(Y)
+    tol = 1.1 * (1e-5 * T + 1e-6) + 1e-6 * np.abs(O) + 1e-12
+    sy = out_scale(O, fy)
+    packed, sw_t, _ = gpu_pack(w, fw, None, want_codes=False)
+    Cp, Np = B.fpq_padded_channels(Cin), B.fpq_padded_channels(Cout)
+    codes_in = torch.empty(Bn * H * W * Cp, dtype=torch.uint8, device=DEV)
+    B.fpq_quantize_nhwc(dev(x), fx, sx, None, codes_in)
+    buf = torch.full((M * Np + 32,), 0xEE, dtype=torch.uint8, device=DEV)
+    ws = torch.empty(max(256, B.fpq_conv2d_workspace_size(Bn, Cin, H, W, Cout, k, k, stride, pad, 0)), dtype=torch.uint8,
+                     device=DEV)
+    B.fpq_conv2d_codes_out(codes_in, 0, fx, sx, None, packed, fw, sw_t, dev(bias), fy, sy, None, buf[16:], Bn, Cin, H, W,
+                           Cout, k, k, stride, pad, B.FPQ_ACC_FP32 | B.FPQ_ACT_SILU, ws)
+    torch.cuda.synchronize()
+    hb = buf.cpu().numpy()
+    assert np.all(hb[:16] == 0xEE) and np.all(hb[16 + M * Np:] == 0xEE)
+    got = hb[16:16 + M * Np].reshape(M, Np)
+    assert np.all(got[:, Cout:] == 0)
+    check_codes_interval(got[:, :Cout], O, tol, fy, sy, "conv silu then codes %s" % (case,))
+
+
 CONVS = [  # B, Cin, H, W, Cout, k, stride, pad: generic kernels, large tile, large tile with split K
     (2, 4, 9, 7, 5, 3, 1, 1), (1, 20, 6, 6, 33, 3, 2, 1), (2, 32, 5, 5, 64, 1, 1, 0), (1, 48, 12, 10, 130, 3, 1, 0),
     (2, 320, 64, 64, 320, 3, 1, 1), (2, 64, 65, 63, 160, 3, 2, 1), (1, 640, 16, 16, 160, 3, 1, 1), (8, 320, 32, 32, 320, 1, 1, 0),
@@ -203,3 +295,12 @@ def test_codes_out_argument_checks():
                                 None) == -8
     assert L.fpq_gemm_codes_out(P, 0, f, 1.0, None, P, f, P, None, f, 1.0, None, C.c_void_p(p.data_ptr() + 4), 8, 8, 32, 0,
                                 None, 0, None) == -5
+    # activations: only with codes out, one at a time, the gated one for linear layers with N % 32 == 0
+    y = torch.zeros(64, device=DEV)
+    Y = C.c_void_p(y.data_ptr())
+    assert L.fpq_gemm(P, 0, f, 1.0, None, P, f, P, None, Y, 8, 8, 32, B.FPQ_ACT_SILU, None, 0, None) == -8
+    assert L.fpq_gemm_codes_out(P, 0, f, 1.0, None, P, f, P, None, f, 1.0, None, P, 8, 8, 32, B.FPQ_ACT_GEGLU, None, 0, None) == -8
+    assert L.fpq_gemm_codes_out(P, 0, f, 1.0, None, P, f, P, None, f, 1.0, None, P, 8, 32, 32,
+                                B.FPQ_ACT_GEGLU | B.FPQ_ACT_SILU, None, 0, None) == -8
+    assert L.fpq_conv2d_codes_out(P, 0, f, 1.0, None, P, f, P, None, f, 1.0, None, P, 1, 16, 4, 4, 32, 1, 1, 1, 0,
+                                  B.FPQ_ACT_GEGLU, None, 0, None) == -8

@@ -640,3 +640,33 @@ def test_requantize_bounds_bracket_the_result_and_close_up_away_from_boundaries(
     assert np.all(lo[n:] != hi[n:])                                             # undecided: the tolerance spans the midpoint
     # the two bounds are neighbours on the grid there
     assert np.all(np.abs(np.searchsorted(g, vhi[n:]) - np.searchsorted(g, vlo[n:])) == 1)
+
+
+def test_activations_against_torch_and_closed_forms():
+    rng = np.random.default_rng(17)
+    x = np.concatenate([rng.normal(0, 3, 5000), [0.0, -0.0, 1e-30, -1e-30, 40.0, -40.0, 700.0, -700.0]])
+    t = torch.from_numpy(x)
+    assert np.allclose(oracle.silu(x), torch.nn.functional.silu(t).numpy(), rtol=1e-14, atol=1e-300)
+    # torch forms 1 + erf, which cancels on the negative side: absolute agreement to an ulp of 1 times |x| there
+    tg = torch.nn.functional.gelu(t).numpy()
+    assert np.all(np.abs(oracle.gelu(x) - tg) <= 1e-12 * np.abs(tg) + 3e-16 * np.abs(x))
+    # sigmoid(x) + sigmoid(-x) = 1 and Phi(x) + Phi(-x) = 1:
+    assert np.allclose(oracle.silu(x) - oracle.silu(-x), x, rtol=1e-13, atol=1e-300)
+    # (the sums are differences of two terms of size |x| / 2: tolerance relative to |x|)
+    assert np.all(np.abs(oracle.silu(x) + oracle.silu(-x) - x * np.tanh(x / 2)) <= 1e-15 * np.abs(x))
+    assert np.allclose(oracle.gelu(x) - oracle.gelu(-x), x, rtol=1e-13, atol=1e-300)
+    from math import erf, sqrt
+    assert np.all(np.abs(oracle.gelu(x) + oracle.gelu(-x) - np.array([v * erf(v / sqrt(2)) for v in x.tolist()])) <= 1e-15 * np.abs(x))
+
+
+def test_geglu_pairs_columns_in_blocks_of_sixteen():
+    rng = np.random.default_rng(19)
+    V = rng.normal(0, 2, (5, 96))
+    out = oracle.geglu(V)
+    assert out.shape == (5, 48)
+    for m in range(5):
+        for o in range(48):
+            blk, i = divmod(o, 16)
+            a, g = V[m, 32 * blk + i], V[m, 32 * blk + 16 + i]
+            want = a * 0.5 * g * (1 + math.erf(g / math.sqrt(2)))
+            assert abs(out[m, o] - want) <= 1e-12 * max(1.0, abs(want))
