@@ -141,6 +141,30 @@ int fpq_search_format(const float *x, size_t n, const int32_t *ebits, const int3
                       int n_bias, float *mse_out, fpq_search_result *result, void *workspace,
                       size_t workspace_bytes, void *stream);
 
+/* ---- gradient-based rounding learning for low-bitwidth weights (Section V-B, Eq. (10)-(14)) ------
+ *
+ * A linear layer without bias, as in the paper's exposition: weights w[N, K] fp32, one scale sw[n] per
+ * output channel, format f, one learnable parameter alpha[N, K] per weight, calibration activations
+ * a[M, K] in full precision.  With y' the clipped weight on the format's axis (fl32(w * fl32(1 / sw)),
+ * Eq. (6)), s its step (Eq. (9)) and fl = floor(y' / s):
+ *   Wq(alpha) = clamp(s * (fl + sigmoid(alpha)), -c, c) * sw                  (Eq. (12) with the sigmoid)
+ *   loss = mean_{M,N}((a Wq^T - a w^T)^2) + reg_weight * mean_{N,K}(1 - (2 |sigmoid(alpha) - 0.5|)^20)
+ * fpq_rl_step performs one step of gradient descent, alpha -= lr * d loss / d alpha (the outer clamp passes
+ * no gradient where it is active), and writes loss_out[0] = the mean squared output error and loss_out[1]
+ * = the mean regulariser of the alpha that came in (device memory, two floats); grad_out[N, K], if not
+ * NULL, receives the gradient used.  fpq_rl_init_alpha sets sigmoid(alpha) to each weight's fractional
+ * position between its two grid neighbours (kept inside [1e-3, 1 - 1e-3]), so that learning starts from
+ * the unquantized weights.  fpq_rl_mask writes the decision used at inference, 1 where
+ * sigmoid(alpha) >= 0.5: the mask that fpq_pack_weights takes.  All products are fp32 on the fp32
+ * matrix instruction.  workspace: fpq_rl_workspace_size bytes, 256-byte aligned, no initialisation. */
+size_t fpq_rl_workspace_size(int64_t M, int64_t N, int64_t K);
+int fpq_rl_init_alpha(const float *w, const float *sw, int64_t N, int64_t K, fpq_format_t f, float *alpha,
+                      void *stream);
+int fpq_rl_step(const float *w, const float *sw, int64_t N, int64_t K, fpq_format_t f, float *alpha,
+                const float *a, int64_t M, float lr, float reg_weight, float *loss_out, float *grad_out,
+                void *workspace, size_t workspace_bytes, void *stream);
+int fpq_rl_mask(const float *alpha, size_t n, uint8_t *mask, void *stream);
+
 /* ---- sparsity (Section VI, "Sparsity"): how many values of a tensor are zero ---------------- */
 
 /* Counts the zeros among the n elements of x and writes the count to count_out (one 64-bit unsigned

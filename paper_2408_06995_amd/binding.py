@@ -89,6 +89,14 @@ def lib():
     L.fpq_conv2d_codes_out.restype = i32
     L.fpq_conv2d_codes_out.argtypes = ([vp, i32, F, fl, f32p, vp, F, f32p, f32p, F, fl, f32p, u8p] + [i64] * 5 + [i32] * 5 +
                                        [vp, sz, vp])
+    L.fpq_rl_workspace_size.restype = sz
+    L.fpq_rl_workspace_size.argtypes = [i64, i64, i64]
+    L.fpq_rl_init_alpha.restype = i32
+    L.fpq_rl_init_alpha.argtypes = [f32p, f32p, i64, i64, F, f32p, vp]
+    L.fpq_rl_step.restype = i32
+    L.fpq_rl_step.argtypes = [f32p, f32p, i64, i64, F, f32p, f32p, i64, fl, fl, f32p, f32p, vp, sz, vp]
+    L.fpq_rl_mask.restype = i32
+    L.fpq_rl_mask.argtypes = [f32p, sz, u8p, vp]
     L.fpq_count_zeros_workspace_size.restype = sz
     L.fpq_count_zeros_workspace_size.argtypes = [sz]
     L.fpq_count_zeros.restype = i32
@@ -101,7 +109,8 @@ EXPORTS = ["fpq_strerror", "fpq_format_max", "fpq_format_check", "fpq_bias_to_sc
            "fpq_absmax_workspace_size", "fpq_absmax", "fpq_quantize", "fpq_padded_channels", "fpq_quantize_nhwc",
            "fpq_dequantize", "fpq_packed_size", "fpq_pack_weights", "fpq_gemm_workspace_size", "fpq_gemm",
            "fpq_conv2d_workspace_size", "fpq_conv2d", "fpq_search_workspace_size", "fpq_search_format",
-           "fpq_count_zeros_workspace_size", "fpq_count_zeros", "fpq_gemm_codes_out", "fpq_conv2d_codes_out"]
+           "fpq_count_zeros_workspace_size", "fpq_count_zeros", "fpq_gemm_codes_out", "fpq_conv2d_codes_out",
+           "fpq_rl_workspace_size", "fpq_rl_init_alpha", "fpq_rl_step", "fpq_rl_mask"]
 
 
 def fmt(f):
@@ -261,3 +270,23 @@ def fpq_conv2d_codes_out(x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, f
                                       _ptr(sw), _ptr(bias), fmt(fy), float(sy), _ptr(sy_dev), _ptr(yq), B, Cin, H, W,
                                       Cout, kh, kw, stride, pad, int(acc_mode), _ptr(workspace), wb, _stream()),
            "fpq_conv2d_codes_out")
+
+
+def fpq_rl_workspace_size(M, N, K):
+    return lib().fpq_rl_workspace_size(M, N, K)
+
+
+def fpq_rl_init_alpha(w, sw, f, alpha):
+    N, K = w.shape
+    _check(lib().fpq_rl_init_alpha(_ptr(w), _ptr(sw), N, K, fmt(f), _ptr(alpha), _stream()), "fpq_rl_init_alpha")
+
+
+def fpq_rl_step(w, sw, f, alpha, a, lr, reg_weight, loss_out, grad_out, workspace):
+    N, K = w.shape
+    _check(lib().fpq_rl_step(_ptr(w), _ptr(sw), N, K, fmt(f), _ptr(alpha), _ptr(a), a.shape[0], float(lr), float(reg_weight),
+                             _ptr(loss_out), _ptr(grad_out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                             _stream()), "fpq_rl_step")
+
+
+def fpq_rl_mask(alpha, mask):
+    _check(lib().fpq_rl_mask(_ptr(alpha), alpha.numel(), _ptr(mask), _stream()), "fpq_rl_mask")

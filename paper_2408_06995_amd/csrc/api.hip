@@ -170,6 +170,53 @@ int fpq_absmax(const float* x, size_t n, float maxval, float* absmax_out, float*
                          static_cast<hipStream_t>(stream));
 }
 
+size_t fpq_rl_workspace_size(int64_t M, int64_t N, int64_t K)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    return rl_workspace_bytes(M, N, K);
+}
+
+static int rl_check(const float* w, const float* sw, int64_t N, int64_t K, fpq_format_t f, QParams* q)
+{
+    int st = resolve_format(f, q);
+    if (st) return st;
+    if (N <= 0 || K <= 0 || N * K >= (int64_t)1 << 31) return FPQ_ERR_SHAPE;
+    if (!w || !sw) return FPQ_ERR_NULL;
+    return FPQ_OK;
+}
+
+int fpq_rl_init_alpha(const float* w, const float* sw, int64_t N, int64_t K, fpq_format_t f, float* alpha, void* stream)
+{
+    QParams q;
+    int st = rl_check(w, sw, N, K, f, &q);
+    if (st) return st;
+    if (!alpha) return FPQ_ERR_NULL;
+    return launch_rl_init(w, sw, N, K, q, alpha, static_cast<hipStream_t>(stream));
+}
+
+int fpq_rl_mask(const float* alpha, size_t n, uint8_t* mask, void* stream)
+{
+    if (n && (!alpha || !mask)) return FPQ_ERR_NULL;
+    if (n == 0) return FPQ_OK;
+    return launch_rl_mask(alpha, n, mask, static_cast<hipStream_t>(stream));
+}
+
+int fpq_rl_step(const float* w, const float* sw, int64_t N, int64_t K, fpq_format_t f, float* alpha, const float* a,
+                int64_t M, float lr, float reg_weight, float* loss_out, float* grad_out, void* workspace,
+                size_t workspace_bytes, void* stream)
+{
+    QParams q;
+    int st = rl_check(w, sw, N, K, f, &q);
+    if (st) return st;
+    if (M <= 0 || M * N >= (int64_t)1 << 31 || M >= (int64_t)1 << 23) return FPQ_ERR_SHAPE;
+    if (!alpha || !a || !loss_out || !workspace) return FPQ_ERR_NULL;
+    if (!(lr >= 0.0f) || isinf(lr) || !(reg_weight >= 0.0f) || isinf(reg_weight)) return FPQ_ERR_SCALE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255) return FPQ_ERR_ALIGN;
+    if (workspace_bytes < rl_workspace_bytes(M, N, K)) return FPQ_ERR_WORKSPACE;
+    return launch_rl_step(w, sw, N, K, q, alpha, a, M, lr, reg_weight, loss_out, grad_out, workspace,
+                          static_cast<hipStream_t>(stream));
+}
+
 size_t fpq_count_zeros_workspace_size(size_t) { return 1024 * sizeof(unsigned long long); }
 
 int fpq_count_zeros(const void* x, int x_kind, size_t n, fpq_format_t f, uint64_t* count_out, void* workspace,

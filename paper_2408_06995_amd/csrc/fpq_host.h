@@ -179,6 +179,13 @@ static inline int search_blocks(size_t n)
 int launch_search(const float* x, size_t n, const SearchArgs& a, const float* absmax_dev, float* partial,
                   float* mse_out, fpq_search_result* result, hipStream_t st);
 
+// Rounding learning (Section V-B): launchers of rounding.hip.
+size_t rl_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int launch_rl_init(const float* w, const float* sw, int64_t N, int64_t K, const QParams& q, float* alpha, hipStream_t st);
+int launch_rl_mask(const float* alpha, size_t n, uint8_t* mask, hipStream_t st);
+int launch_rl_step(const float* w, const float* sw, int64_t N, int64_t K, const QParams& q, float* alpha, const float* a,
+                   int64_t M, float lr, float reg_weight, float* loss_out, float* grad_out, void* workspace, hipStream_t st);
+
 // Zero count (Section VI, "Sparsity"): blocks of the counting pass, each with a contiguous share of the bytes.
 static inline int count_zeros_parts(size_t nbytes)
 {
