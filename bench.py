@@ -448,6 +448,29 @@ def main():
         out["zero_count"] = {"code_bytes": 4 * n, "codes_GB/s": round(zc_gbs, 1), "codes_frac": round(zc_gbs / PEAK_HBM_GBS, 4),
                              "fp32_GB/s": round(zf_gbs, 1), "fp32_frac": round(zf_gbs / PEAK_HBM_GBS, 4)}
         del bufs, codes, cbig
+        # one step of rounding learning (Section V-B) on a 1280 x 1280 linear layer with 8192 calibration rows, E2M1
+        # weights: two fp32 contractions of 2 M N K flops each, on the fp32 matrix instruction (peak 157.3 TFLOP/s)
+        rN, rK, rM = 1280, 1280, 8192
+        rw = synth.weights_torch((rN, rK), 5, dev)
+        rsw = (rw.abs().amax(dim=1) / FW4[3]).contiguous()
+        ra = synth.activations_torch((rM, rK), 6, dev)
+        ral = torch.empty((rN, rK), device=dev)
+        B.fpq_rl_init_alpha(rw, rsw, FW4, ral)
+        rloss = torch.zeros(2, device=dev)
+        rws = torch.empty(B.fpq_rl_workspace_size(rM, rN, rK), dtype=torch.uint8, device=dev)
+        for _ in range(3):
+            B.fpq_rl_step(rw, rsw, FW4, ral, ra, 1000.0, 0.01, rloss, None, rws)
+        e0.record()
+        for _ in range(20):
+            B.fpq_rl_step(rw, rsw, FW4, ral, ra, 1000.0, 0.01, rloss, None, rws)
+        e1.record()
+        e1.synchronize()
+        r_ms = e0.elapsed_time(e1) / 20
+        r_tf = 4.0 * rM * rN * rK / (r_ms * 1e-3) / 1e12
+        out["rounding_learning_step"] = {"N": rN, "K": rK, "M": rM, "ms": round(r_ms, 3), "TFLOP/s": round(r_tf, 1),
+                                         "peak_fp32_mfma": 157.3, "frac": round(r_tf / 157.3, 4),
+                                         "mse_and_regulariser_after_23_steps": ["%.4e" % float(v) for v in rloss.cpu().tolist()]}
+        del rw, ra, ral, rws
 
     if not args.no_cpu_baseline:
         import oracle
