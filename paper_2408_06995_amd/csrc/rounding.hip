@@ -149,20 +149,20 @@ __global__ __launch_bounds__(256) void rl_mask_kernel(const float* __restrict__ 
 // KCONTIG = true:  pk = 1 (rows of P and Q run along k: C = P Q^T),
 // KCONTIG = false: pi = 1 (rows of the stored matrices run along i / j: C = P'^T Q' with P' = [Kc, I], Q' = [Kc, J]).
 // A workgroup of four wavefronts owns a T x T tile of C (T = 128 or 64; each wavefront a T/2 x T/2 quarter, as
-// (T/64)^2 blocks of the 32x32x2 fp32 matrix instruction) and walks k in steps of 16 through LDS tiles laid out
-// [k][row], so that the lanes of an MFMA operand read consecutive words.  The global loads of step t + 1 are in
-// flight while step t is computed.
+// (T/64)^2 blocks of the 32x32x2 fp32 matrix instruction) and walks k in steps of 16 through two LDS buffers laid out
+// [k][row], so that the lanes of an MFMA operand read consecutive words.  The global loads of step t + 1 (16 bytes
+// per lane where alignment allows) are in flight while step t is computed.
 template <int T, bool KCONTIG>
 __global__ __launch_bounds__(256) void sgemm_kernel(const float* __restrict__ p, long pstride, const float* __restrict__ qm,
                                                     long qstride, int I, int J, int Kc, float scale,
-                                                    float* __restrict__ c, long cstride)
+                                                    float* __restrict__ c, long cstride, int vec)
 {
     constexpr int BK = 16;
     constexpr int LD = T + 4;
     constexpr int NB = T / 64;                     // 32-row blocks per wave and direction
-    constexpr int PER = T * BK / 256;              // elements of each operand tile per thread and step
-    __shared__ float ps[BK * LD];
-    __shared__ float qs[BK * LD];
+    constexpr int PER4 = T * BK / 4 / 256;         // 16-byte groups of each operand tile per thread and step
+    __shared__ __attribute__((aligned(16))) float ps[2][BK * LD];
+    __shared__ __attribute__((aligned(16))) float qs[2][BK * LD];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
     const int wi = wave >> 1, wj = wave & 1;
@@ -176,51 +176,77 @@ __global__ __launch_bounds__(256) void sgemm_kernel(const float* __restrict__ p,
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
 
-    // element e of a thread's share of a tile: KCONTIG: row = idx / BK, k = idx % BK (k fastest in memory);
-    // otherwise: k = idx / T, row = idx % T (rows fastest in memory); idx = e * 256 + tid
-    float pr[PER], qr[PER];
+    // A thread's share of a tile: groups of four elements that are consecutive in memory, group index
+    // e * 256 + tid; KCONTIG: row = group / (BK / 4), k = 4 (group % (BK / 4)) .. + 3; otherwise
+    // k = group / (T / 4), row = 4 (group % (T / 4)) .. + 3.  `vec` (host-checked: 16-byte aligned bases, strides
+    // that are multiples of 4) allows one 16-byte load for a group that lies inside the matrix; anything else is
+    // read element by element with zeros outside.
+    float4 pr[PER4], qr[PER4];
+    auto load_group = [&](const float* base, long stride, int o0, int O, int k0, int group) -> float4 {
+        const int row = KCONTIG ? group / (BK / 4) : 4 * (group % (T / 4));
+        const int k = KCONTIG ? 4 * (group % (BK / 4)) : group / (T / 4);
+        float v[4];
+        if (KCONTIG) {
+            const float* src = base + (long)(o0 + row) * stride + (k0 + k);
+            if (vec && o0 + row < O && k0 + k + 3 < Kc) return *reinterpret_cast<const float4*>(src);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) v[t] = (o0 + row < O && k0 + k + t < Kc) ? src[t] : 0.0f;
+        } else {
+            const float* src = base + (long)(k0 + k) * stride + (o0 + row);
+            if (vec && k0 + k < Kc && o0 + row + 3 < O) return *reinterpret_cast<const float4*>(src);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) v[t] = (k0 + k < Kc && o0 + row + t < O) ? src[t] : 0.0f;
+        }
+        return make_float4(v[0], v[1], v[2], v[3]);
+    };
     auto load = [&](int k0) {
 #pragma unroll
-        for (int e = 0; e < PER; ++e) {
-            const int idx = e * 256 + tid;
-            const int row = KCONTIG ? idx / BK : idx % T;
-            const int k = KCONTIG ? idx % BK : idx / T;
-            const bool kin = k0 + k < Kc;
-            const long off_p = KCONTIG ? (long)(i0 + row) * pstride + (k0 + k) : (long)(k0 + k) * pstride + (i0 + row);
-            const long off_q = KCONTIG ? (long)(j0 + row) * qstride + (k0 + k) : (long)(k0 + k) * qstride + (j0 + row);
-            pr[e] = (kin && i0 + row < I) ? p[off_p] : 0.0f;
-            qr[e] = (kin && j0 + row < J) ? qm[off_q] : 0.0f;
+        for (int e = 0; e < PER4; ++e) {
+            pr[e] = load_group(p, pstride, i0, I, k0, e * 256 + tid);
+            qr[e] = load_group(qm, qstride, j0, J, k0, e * 256 + tid);
         }
     };
-    auto store = [&]() {
+    auto store = [&](int buf) {
 #pragma unroll
-        for (int e = 0; e < PER; ++e) {
-            const int idx = e * 256 + tid;
-            const int row = KCONTIG ? idx / BK : idx % T;
-            const int k = KCONTIG ? idx % BK : idx / T;
-            ps[k * LD + row] = pr[e];
-            qs[k * LD + row] = qr[e];
+        for (int e = 0; e < PER4; ++e) {
+            const int group = e * 256 + tid;
+            if (KCONTIG) {
+                const int row = group / (BK / 4), k = 4 * (group % (BK / 4));
+                ps[buf][k * LD + row] = pr[e].x; ps[buf][(k + 1) * LD + row] = pr[e].y;
+                ps[buf][(k + 2) * LD + row] = pr[e].z; ps[buf][(k + 3) * LD + row] = pr[e].w;
+                qs[buf][k * LD + row] = qr[e].x; qs[buf][(k + 1) * LD + row] = qr[e].y;
+                qs[buf][(k + 2) * LD + row] = qr[e].z; qs[buf][(k + 3) * LD + row] = qr[e].w;
+            } else {
+                const int k = group / (T / 4), row = 4 * (group % (T / 4));
+                *reinterpret_cast<float4*>(&ps[buf][k * LD + row]) = pr[e];
+                *reinterpret_cast<float4*>(&qs[buf][k * LD + row]) = qr[e];
+            }
         }
     };
 
+    // two LDS buffers: step t is computed from one while step t + 1 is stored into the other; one barrier per step
     load(0);
+    store(0);
+    __syncthreads();
+    int buf = 0;
     for (int k0 = 0; k0 < Kc; k0 += BK) {
-        __syncthreads();                // the previous step's reads are done
-        store();
-        __syncthreads();
-        if (k0 + BK < Kc) load(k0 + BK);
+        const bool more = k0 + BK < Kc;
+        if (more) load(k0 + BK);
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
             float pa[NB], qb[NB];
 #pragma unroll
-            for (int a = 0; a < NB; ++a) pa[a] = ps[(kk + g) * LD + wi * (T / 2) + 32 * a + l32];
+            for (int a = 0; a < NB; ++a) pa[a] = ps[buf][(kk + g) * LD + wi * (T / 2) + 32 * a + l32];
 #pragma unroll
-            for (int b = 0; b < NB; ++b) qb[b] = qs[(kk + g) * LD + wj * (T / 2) + 32 * b + l32];
+            for (int b = 0; b < NB; ++b) qb[b] = qs[buf][(kk + g) * LD + wj * (T / 2) + 32 * b + l32];
 #pragma unroll
             for (int a = 0; a < NB; ++a)
 #pragma unroll
                 for (int b = 0; b < NB; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[a], qb[b], acc[a][b], 0, 0, 0);
         }
+        if (more) store(buf ^ 1);       // nobody reads that buffer: its last readers passed the barrier of the previous step
+        __syncthreads();
+        buf ^= 1;
     }
     // acc[a][b][r]: row 8 (r / 4) + 4 g + r % 4 of the block (operand P), column l32 (operand Q)
 #pragma unroll
@@ -240,13 +266,15 @@ template <bool KCONTIG>
 void launch_sgemm(const float* p, long pstride, const float* q, long qstride, int I, int J, int Kc, float scale, float* c,
                   long cstride, hipStream_t st)
 {
+    const int vec = ((reinterpret_cast<uintptr_t>(p) | reinterpret_cast<uintptr_t>(q)) & 15) == 0 && pstride % 4 == 0 &&
+                    qstride % 4 == 0;
     const long big = (long)((I + 127) / 128) * ((J + 127) / 128);
     if (big >= 256)
         hipLaunchKernelGGL((sgemm_kernel<128, KCONTIG>), dim3((J + 127) / 128, (I + 127) / 128), dim3(256), 0, st, p, pstride, q,
-                           qstride, I, J, Kc, scale, c, cstride);
+                           qstride, I, J, Kc, scale, c, cstride, vec);
     else
         hipLaunchKernelGGL((sgemm_kernel<64, KCONTIG>), dim3((J + 63) / 64, (I + 63) / 64), dim3(256), 0, st, p, pstride, q,
-                           qstride, I, J, Kc, scale, c, cstride);
+                           qstride, I, J, Kc, scale, c, cstride, vec);
 }
 
 int blocks_for(size_t n)
