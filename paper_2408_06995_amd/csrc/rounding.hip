@@ -102,8 +102,8 @@ __global__ __launch_bounds__(256) void rl_loss_kernel(const float* __restrict__ 
 
 // alpha -= lr * (g * dWq/dalpha + reg_weight * dreg/dalpha); the gradient itself goes to grad_out when asked for.
 __global__ __launch_bounds__(256) void rl_update_kernel(const float* __restrict__ w, const float* __restrict__ sw,
-                                                        float* __restrict__ alpha, const float* __restrict__ g, size_t n,
-                                                        int K, QParams q, float lr, float reg_scale,
+                                                        float* __restrict__ alpha, const float* __restrict__ g, int gslices,
+                                                        size_t n, int K, QParams q, float lr, float reg_scale,
                                                         float* __restrict__ grad_out)
 {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
@@ -118,7 +118,9 @@ __global__ __launch_bounds__(256) void rl_update_kernel(const float* __restrict_
         const float u = 2.0f * fabsf(dv);
         const float u2 = u * u, u4 = u2 * u2, u8 = u4 * u4, u16 = u8 * u8;
         const float dlam = -20.0f * (u16 * u2 * u) * 2.0f * (dv > 0.0f ? 1.0f : (dv < 0.0f ? -1.0f : 0.0f)) * ds;
-        const float grad = g[i] * dwq + reg_scale * dlam;
+        float gi = g[i];                                     // d mse / d Wq: the slices of the product, in order
+        for (int z = 1; z < gslices; ++z) gi += g[(size_t)z * n + i];
+        const float grad = gi * dwq + reg_scale * dlam;
         if (grad_out) grad_out[i] = grad;
         alpha[i] = a - lr * grad;
     }
@@ -155,7 +157,7 @@ __global__ __launch_bounds__(256) void rl_mask_kernel(const float* __restrict__ 
 template <int T, bool KCONTIG>
 __global__ __launch_bounds__(256) void sgemm_kernel(const float* __restrict__ p, long pstride, const float* __restrict__ qm,
                                                     long qstride, int I, int J, int Kc, float scale,
-                                                    float* __restrict__ c, long cstride, int vec)
+                                                    float* __restrict__ c, long cstride, int vec, int kslice)
 {
     constexpr int BK = 16;
     constexpr int LD = T + 4;
@@ -167,6 +169,10 @@ __global__ __launch_bounds__(256) void sgemm_kernel(const float* __restrict__ p,
     const int l32 = lane & 31, g = lane >> 5;
     const int wi = wave >> 1, wj = wave & 1;
     const int i0 = blockIdx.y * T, j0 = blockIdx.x * T;
+    // slice blockIdx.z of the contraction (kslice steps of k each, a multiple of BK) writes its own copy of C
+    const int kbeg = blockIdx.z * kslice;
+    const int kend = kbeg + kslice < Kc ? kbeg + kslice : Kc;
+    c += (size_t)blockIdx.z * (size_t)I * cstride;
 
     v16f acc[NB][NB];
 #pragma unroll
@@ -188,14 +194,14 @@ __global__ __launch_bounds__(256) void sgemm_kernel(const float* __restrict__ p,
         float v[4];
         if (KCONTIG) {
             const float* src = base + (long)(o0 + row) * stride + (k0 + k);
-            if (vec && o0 + row < O && k0 + k + 3 < Kc) return *reinterpret_cast<const float4*>(src);
+            if (vec && o0 + row < O && k0 + k + 3 < kend) return *reinterpret_cast<const float4*>(src);
 #pragma unroll
-            for (int t = 0; t < 4; ++t) v[t] = (o0 + row < O && k0 + k + t < Kc) ? src[t] : 0.0f;
+            for (int t = 0; t < 4; ++t) v[t] = (o0 + row < O && k0 + k + t < kend) ? src[t] : 0.0f;
         } else {
             const float* src = base + (long)(k0 + k) * stride + (o0 + row);
-            if (vec && k0 + k < Kc && o0 + row + 3 < O) return *reinterpret_cast<const float4*>(src);
+            if (vec && k0 + k < kend && o0 + row + 3 < O) return *reinterpret_cast<const float4*>(src);
 #pragma unroll
-            for (int t = 0; t < 4; ++t) v[t] = (k0 + k < Kc && o0 + row + t < O) ? src[t] : 0.0f;
+            for (int t = 0; t < 4; ++t) v[t] = (k0 + k < kend && o0 + row + t < O) ? src[t] : 0.0f;
         }
         return make_float4(v[0], v[1], v[2], v[3]);
     };
@@ -225,12 +231,12 @@ __global__ __launch_bounds__(256) void sgemm_kernel(const float* __restrict__ p,
     };
 
     // two LDS buffers: step t is computed from one while step t + 1 is stored into the other; one barrier per step
-    load(0);
+    load(kbeg);
     store(0);
     __syncthreads();
     int buf = 0;
-    for (int k0 = 0; k0 < Kc; k0 += BK) {
-        const bool more = k0 + BK < Kc;
+    for (int k0 = kbeg; k0 < kend; k0 += BK) {
+        const bool more = k0 + BK < kend;
         if (more) load(k0 + BK);
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
@@ -262,19 +268,32 @@ __global__ __launch_bounds__(256) void sgemm_kernel(const float* __restrict__ p,
         }
 }
 
+// slices > 1: the contraction is cut into that many pieces, piece z writes c + z * I * cstride (the caller adds them up)
 template <bool KCONTIG>
 void launch_sgemm(const float* p, long pstride, const float* q, long qstride, int I, int J, int Kc, float scale, float* c,
-                  long cstride, hipStream_t st)
+                  long cstride, int slices, hipStream_t st)
 {
     const int vec = ((reinterpret_cast<uintptr_t>(p) | reinterpret_cast<uintptr_t>(q)) & 15) == 0 && pstride % 4 == 0 &&
                     qstride % 4 == 0;
-    const long big = (long)((I + 127) / 128) * ((J + 127) / 128);
+    const int kslice = ((Kc + slices - 1) / slices + 15) / 16 * 16;
+    const long big = (long)((I + 127) / 128) * ((J + 127) / 128) * slices;
     if (big >= 256)
-        hipLaunchKernelGGL((sgemm_kernel<128, KCONTIG>), dim3((J + 127) / 128, (I + 127) / 128), dim3(256), 0, st, p, pstride, q,
-                           qstride, I, J, Kc, scale, c, cstride, vec);
+        hipLaunchKernelGGL((sgemm_kernel<128, KCONTIG>), dim3((J + 127) / 128, (I + 127) / 128, slices), dim3(256), 0, st, p,
+                           pstride, q, qstride, I, J, Kc, scale, c, cstride, vec, kslice);
     else
-        hipLaunchKernelGGL((sgemm_kernel<64, KCONTIG>), dim3((J + 63) / 64, (I + 63) / 64), dim3(256), 0, st, p, pstride, q,
-                           qstride, I, J, Kc, scale, c, cstride, vec);
+        hipLaunchKernelGGL((sgemm_kernel<64, KCONTIG>), dim3((J + 63) / 64, (I + 63) / 64, slices), dim3(256), 0, st, p,
+                           pstride, q, qstride, I, J, Kc, scale, c, cstride, vec, kslice);
+}
+
+// Slices of the gradient product (its contraction runs over the M calibration rows, its output is only [N, K]): enough
+// to give the 128-row tile a few hundred workgroups, each slice at least 512 rows deep, at most 8.
+int rl_slices(int64_t M, int64_t N, int64_t K)
+{
+    const int64_t tiles = ((N + 127) / 128) * ((K + 127) / 128);
+    int64_t s = (384 + tiles - 1) / tiles;
+    if (s > M / 512) s = M / 512;
+    if (s > 8) s = 8;
+    return s < 1 ? 1 : (int)s;
 }
 
 int blocks_for(size_t n)
@@ -287,9 +306,9 @@ int blocks_for(size_t n)
 
 size_t rl_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
-    // D [N, K], G [N, K], R [M, N], 2 x 1024 partial sums
+    // D [N, K], R [M, N], 2 x 1024 partial sums, G [slices][N, K]
     auto up = [](size_t v) { return (v + 255) / 256 * 256; };
-    return 2 * up((size_t)N * K * 4) + up((size_t)M * N * 4) + 2 * 4096;
+    return up((size_t)N * K * 4) + up((size_t)M * N * 4) + 2 * 4096 + up((size_t)rl_slices(M, N, K) * N * K * 4);
 }
 
 int launch_rl_init(const float* w, const float* sw, int64_t N, int64_t K, const QParams& q, float* alpha, hipStream_t st)
@@ -311,20 +330,21 @@ int launch_rl_step(const float* w, const float* sw, int64_t N, int64_t K, const 
     auto up = [](size_t v) { return (v + 255) / 256 * 256; };
     uint8_t* ws = static_cast<uint8_t*>(workspace);
     float* d = reinterpret_cast<float*>(ws);
-    float* g = reinterpret_cast<float*>(ws + up((size_t)N * K * 4));
-    float* r = reinterpret_cast<float*>(ws + 2 * up((size_t)N * K * 4));
-    float* regp = reinterpret_cast<float*>(ws + 2 * up((size_t)N * K * 4) + up((size_t)M * N * 4));
+    float* r = reinterpret_cast<float*>(ws + up((size_t)N * K * 4));
+    float* regp = reinterpret_cast<float*>(ws + up((size_t)N * K * 4) + up((size_t)M * N * 4));
     float* sqp = regp + 1024;
+    float* g = sqp + 1024;
+    const int slices = rl_slices(M, N, K);
     const size_t nw = (size_t)N * K, nr = (size_t)M * N;
     const int bw = blocks_for(nw), br = blocks_for(nr);
     hipLaunchKernelGGL(rl_soft_kernel, dim3(bw), dim3(256), 0, st, w, sw, alpha, nw, (int)K, q, d, regp);
     // R[m, n] = sum_k A[m, k] D[n, k]
-    launch_sgemm<true>(a, K, d, K, (int)M, (int)N, (int)K, 1.0f, r, N, st);
+    launch_sgemm<true>(a, K, d, K, (int)M, (int)N, (int)K, 1.0f, r, N, 1, st);
     hipLaunchKernelGGL(rl_sumsq_kernel, dim3(br), dim3(256), 0, st, r, nr, sqp);
     hipLaunchKernelGGL(rl_loss_kernel, dim3(1), dim3(256), 0, st, sqp, br, (double)nr, regp, bw, (double)nw, loss_out);
     // G[n, k] = (2 / (M N)) sum_m R[m, n] A[m, k]
-    launch_sgemm<false>(r, N, a, K, (int)N, (int)K, (int)M, (float)(2.0 / (double)nr), g, K, st);
-    hipLaunchKernelGGL(rl_update_kernel, dim3(bw), dim3(256), 0, st, w, sw, alpha, g, nw, (int)K, q, lr,
+    launch_sgemm<false>(r, N, a, K, (int)N, (int)K, (int)M, (float)(2.0 / (double)nr), g, K, slices, st);
+    hipLaunchKernelGGL(rl_update_kernel, dim3(bw), dim3(256), 0, st, w, sw, alpha, g, slices, nw, (int)K, q, lr,
                        (float)((double)reg_weight / (double)nw), grad_out);
     return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
 }
