@@ -380,7 +380,7 @@ def main():
             del xs, w, cb, yb, yq, wsb
         out["single_layers"] = singles
         # encoding / bias search of Section V-A on one activation tensor (8 x 320 x 64 x 64): 4 FP8 encodings x 111
-        # bias candidates; bound by vector ALU work (see the design notes for the instruction count behind the peak)
+        # bias candidates; bound by vector ALU work: 11 vector instructions per element and candidate (SEARCH_OPS) against the lane-instruction rate of the chip
         xs = synth.activations_torch((8, 320, 64, 64), 3, dev).reshape(-1)
         encs = [(2, 5), (3, 4), (4, 3), (5, 2)]
         s_mse = torch.empty(4 * 111, dtype=torch.float32, device=dev)
