@@ -262,7 +262,7 @@ int fpq_quantize_nhwc(const float* x, int64_t B, int64_t C, int64_t H, int64_t W
     if (st) return st;
     if (!scale_dev && !scale_ok(scale)) return FPQ_ERR_SCALE;
     if (B <= 0 || C <= 0 || H <= 0 || W <= 0) return FPQ_ERR_SHAPE;
-    if (B > 65535 || H * W > (1 << 24) || B * H * W * padded_channels(C) >= (int64_t)1 << 31) return FPQ_ERR_SHAPE;
+    if (B >= (int64_t)1 << 31 || H * W > (1 << 24) || B * H * W * padded_channels(C) >= (int64_t)1 << 31) return FPQ_ERR_SHAPE;
     if (!x || !codes) return FPQ_ERR_NULL;
     if ((reinterpret_cast<uintptr_t>(x) & 3) || (reinterpret_cast<uintptr_t>(codes) & 15)) return FPQ_ERR_ALIGN;
     const ScaleSrc ss{scale, scale_dev, nullptr, 0, 0.0f, nullptr};
@@ -529,7 +529,6 @@ int fpq_gemm(const void* x, int x_is_fp32, fpq_format_t fx, float sx, const floa
              int acc_mode, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (M == 0 && N > 0 && K > 0) return FPQ_OK;
-    if (M > 0 && M > 65535 && x_is_fp32 && padded_channels(K) != K) return FPQ_ERR_UNSUPPORTED;
     return run_layer(nullptr, x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, y, M, K, 1, 1, N, 1, 1, 1, 0, 0, acc_mode,
                      workspace, workspace_bytes, stream);
 }
@@ -549,7 +548,6 @@ int fpq_gemm_codes_out(const void* x, int x_is_fp32, fpq_format_t fx, float sx, 
                        void* stream)
 {
     if (M == 0 && N > 0 && K > 0) return FPQ_OK;
-    if (M > 0 && M > 65535 && x_is_fp32 && padded_channels(K) != K) return FPQ_ERR_UNSUPPORTED;
     const CodesOut out{fy, sy, sy_dev, yq};
     return run_layer(&out, x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, nullptr, M, K, 1, 1, N, 1, 1, 1, 0, 0,
                      acc_mode, workspace, workspace_bytes, stream);

@@ -288,14 +288,15 @@ int launch_quantize(const float* x, size_t n, const QParams& q, bool four_bit, c
 // NCHW), the codes cross an LDS tile, writes run along channels (contiguous in [B,H,W,Cp]).
 // Channels C..Cp-1 receive code 0.  Rows of the tile are 68 bytes so that the four-byte column
 // groups of neighbouring pixels fall into different LDS banks.
-__global__ __launch_bounds__(256) void quantize_nhwc_kernel(const float* __restrict__ x, int C, int Cp, int HW,
+__global__ __launch_bounds__(256) void quantize_nhwc_kernel(const float* __restrict__ x, int B, int C, int Cp, int HW,
                                                             QParams q, ScaleSrc ss, bool stream,
                                                             uint8_t* __restrict__ codes)
 {
     constexpr int LDW = 68;
     __shared__ __attribute__((aligned(16))) uint8_t tile[64 * LDW];
     const float r = block_inv_scale(ss);
-    const int b = blockIdx.z;
+    // images b = blockIdx.z, blockIdx.z + gridDim.z, ... (the grid's third dimension stops at 65535)
+    for (int b = blockIdx.z; b < B; b += gridDim.z) {
     const int c0 = blockIdx.y * 64;
     const int p0 = blockIdx.x * 64;
     const int pq = threadIdx.x & 15;   // pixel quad
@@ -334,6 +335,8 @@ __global__ __launch_bounds__(256) void quantize_nhwc_kernel(const float* __restr
         uint4 v = make_uint4(t4[0], t4[1], t4[2], t4[3]);
         *reinterpret_cast<uint4*>(codes + ((size_t)b * HW + p) * (size_t)Cp + ch) = v;
     }
+    __syncthreads();   // the tile is rewritten for the next image
+    }
 }
 
 int launch_quantize_nhwc(const float* x, int64_t B, int64_t C, int64_t H, int64_t W, const QParams& q,
@@ -341,8 +344,8 @@ int launch_quantize_nhwc(const float* x, int64_t B, int64_t C, int64_t H, int64_
 {
     int Cp = (int)padded_channels(C);
     int HW = (int)(H * W);
-    dim3 grid((HW + 63) / 64, (Cp + 63) / 64, (unsigned)B);
-    hipLaunchKernelGGL(quantize_nhwc_kernel, grid, dim3(256), 0, st, x, (int)C, Cp, HW, q, ss,
+    dim3 grid((HW + 63) / 64, (Cp + 63) / 64, (unsigned)(B < 65535 ? B : 65535));
+    hipLaunchKernelGGL(quantize_nhwc_kernel, grid, dim3(256), 0, st, x, (int)B, (int)C, Cp, HW, q, ss,
                        (size_t)B * C * H * W >= kStreamElems, codes);
     return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
 }

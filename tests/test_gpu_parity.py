@@ -403,6 +403,24 @@ def test_conv_one_hot_taps_exact():
         assert np.array_equal(y.cpu().numpy(), want)
 
 
+def test_fp32_input_with_more_rows_than_a_grid_dimension_and_padded_k():
+    """M > 65535 rows and K not a multiple of 16: the channels-last quantizer walks the rows in several rounds."""
+    M, K, N = 70001, 24, 8
+    fx = fw = synth.E4M3
+    x = synth.activations((M, K), 77)
+    w = synth.weights((N, K), 78)
+    sx, xq, wq, sw = oracle_linear_inputs(x, w, None, fx, fw)
+    packed, sw_t, _ = gpu_pack(w, fw, None, want_codes=False)
+    y = torch.full((M, N), float("nan"), device=DEV)
+    ws = torch.empty(B.fpq_gemm_workspace_size(M, N, K, 1), dtype=torch.uint8, device=DEV)
+    B.fpq_gemm(dev(x), 1, fx, sx, None, packed, fw, sw_t, None, y, M, N, K, B.FPQ_ACC_FP32, ws)
+    torch.cuda.synchronize()
+    Y, T = oracle.gemm(xq, fx, sx, wq, fw, sw)
+    check_close(y.cpu().numpy(), Y, T, what="70001-row fp32 input")
+    codes = ws.cpu().numpy()[:M * 32].reshape(M, 32)
+    assert np.array_equal(codes[:, :K], xq) and np.all(codes[:, K:] == 0)
+
+
 # ------------------------------------------------------------------------------ large-tile (N % 160 == 0) kernels
 
 @pytest.mark.parametrize("M,K,N", [(256, 128, 160), (257, 144, 160), (300, 2880, 320), (1000, 320, 480), (512, 6400, 160),
