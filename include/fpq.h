@@ -217,6 +217,14 @@ int fpq_pack_weights(const float *w, int64_t N, int64_t Cin, int kh, int kw, fpq
                      const float *scale, const uint8_t *mask, void *packed, size_t packed_bytes,
                      float *scale_out, uint8_t *codes_out, void *stream);
 
+/* Reads the header of a packed weight buffer back (synchronises `stream`; the only entry point that
+ * waits for the device) and compares it with the arguments a layer call is about to pass: FPQ_OK, or
+ * FPQ_ERR_FORMAT (not a packed buffer, or another format / max value) or FPQ_ERR_SHAPE (other N, Cin,
+ * kh, kw).  The layer calls themselves are asynchronous and do not check the header: passing them a
+ * buffer packed for another shape or format is the caller's error. */
+int fpq_packed_check(const void *packed, int64_t N, int64_t Cin, int kh, int kw, fpq_format_t f,
+                     void *stream);
+
 /* ---- quantized layers: Y = sx * sw[n] * sum_k deq(xq) * deq(wq) (+ bias[n]) ------------- */
 
 /* Linear layer.  x: x_is_fp32 == 0: codes [M, K], one per byte, K % 16 == 0, 16-byte aligned;

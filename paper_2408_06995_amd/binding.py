@@ -72,6 +72,8 @@ def lib():
     L.fpq_packed_size.argtypes = [i64, i64, i32, i32, F]
     L.fpq_pack_weights.restype = i32
     L.fpq_pack_weights.argtypes = [f32p, i64, i64, i32, i32, F, f32p, u8p, vp, sz, f32p, u8p, vp]
+    L.fpq_packed_check.restype = i32
+    L.fpq_packed_check.argtypes = [vp, i64, i64, i32, i32, F, vp]
     L.fpq_gemm_workspace_size.restype = sz
     L.fpq_gemm_workspace_size.argtypes = [i64, i64, i64, i32]
     L.fpq_gemm.restype = i32
@@ -110,7 +112,7 @@ EXPORTS = ["fpq_strerror", "fpq_format_max", "fpq_format_check", "fpq_bias_to_sc
            "fpq_dequantize", "fpq_packed_size", "fpq_pack_weights", "fpq_gemm_workspace_size", "fpq_gemm",
            "fpq_conv2d_workspace_size", "fpq_conv2d", "fpq_search_workspace_size", "fpq_search_format",
            "fpq_count_zeros_workspace_size", "fpq_count_zeros", "fpq_gemm_codes_out", "fpq_conv2d_codes_out",
-           "fpq_rl_workspace_size", "fpq_rl_init_alpha", "fpq_rl_step", "fpq_rl_mask"]
+           "fpq_rl_workspace_size", "fpq_rl_init_alpha", "fpq_rl_step", "fpq_rl_mask", "fpq_packed_check"]
 
 
 def fmt(f):
@@ -290,3 +292,8 @@ def fpq_rl_step(w, sw, f, alpha, a, lr, reg_weight, loss_out, grad_out, workspac
 
 def fpq_rl_mask(alpha, mask):
     _check(lib().fpq_rl_mask(_ptr(alpha), alpha.numel(), _ptr(mask), _stream()), "fpq_rl_mask")
+
+
+def fpq_packed_check(packed, N, Cin, kh, kw, f):
+    """Status code (0 = the buffer was packed for these arguments); synchronises the current stream."""
+    return lib().fpq_packed_check(_ptr(packed), N, Cin, kh, kw, fmt(f), _stream())

@@ -319,6 +319,22 @@ int fpq_pack_weights(const float* w, int64_t N, int64_t Cin, int kh, int kw, fpq
                                static_cast<uint8_t*>(packed) + kPackedRowsOffset, scale_out, codes_out, s);
 }
 
+int fpq_packed_check(const void* packed, int64_t N, int64_t Cin, int kh, int kw, fpq_format_t f, void* stream)
+{
+    QParams q;
+    int st = resolve_format(f, &q);
+    if (st) return st;
+    if (!packed) return FPQ_ERR_NULL;
+    PackedHeader h;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(&h, packed, sizeof h, hipMemcpyDeviceToHost, s) != hipSuccess) return FPQ_ERR_LAUNCH;
+    if (hipStreamSynchronize(s) != hipSuccess) return FPQ_ERR_LAUNCH;
+    if (h.magic != kPackedMagic || h.layout != 1) return FPQ_ERR_FORMAT;
+    if (h.ebits != f.ebits || h.mbits != f.mbits || h.bias != f.bias || h.maxval != q.c) return FPQ_ERR_FORMAT;
+    if (h.N != N || h.Cin != Cin || h.kh != kh || h.kw != kw) return FPQ_ERR_SHAPE;
+    return FPQ_OK;
+}
+
 // workspace of the search: [1024 partial maxima][absmax, 256 bytes][per-block error sums]
 size_t fpq_search_workspace_size(size_t n, int n_enc, int n_bias)
 {

@@ -403,6 +403,17 @@ def test_conv_one_hot_taps_exact():
         assert np.array_equal(y.cpu().numpy(), want)
 
 
+def test_packed_header_check():
+    w = synth.weights((40, 24, 3, 3), 5)
+    packed, _, _ = gpu_pack(w, synth.E2M1, None, want_codes=False)
+    assert B.fpq_packed_check(packed, 40, 24, 3, 3, synth.E2M1) == 0
+    assert B.fpq_packed_check(packed, 40, 24, 3, 3, synth.E4M3) == -2          # another format
+    assert B.fpq_packed_check(packed, 40, 24, 3, 3, (2, 1, 1, 4.0)) == -2      # another max value
+    assert B.fpq_packed_check(packed, 41, 24, 3, 3, synth.E2M1) == -4
+    assert B.fpq_packed_check(packed, 40, 24, 1, 1, synth.E2M1) == -4
+    assert B.fpq_packed_check(torch.zeros(512, dtype=torch.uint8, device=DEV), 40, 24, 3, 3, synth.E2M1) == -2
+
+
 def test_fp32_input_with_more_rows_than_a_grid_dimension_and_padded_k():
     """M > 65535 rows and K not a multiple of 16: the channels-last quantizer walks the rows in several rounds."""
     M, K, N = 70001, 24, 8
