@@ -157,6 +157,13 @@ int fpq_search_format(const float *x, size_t n, const int32_t *ebits, const int3
  * the unquantized weights.  fpq_rl_mask writes the decision used at inference, 1 where
  * sigmoid(alpha) >= 0.5: the mask that fpq_pack_weights takes.  All products are fp32 on the fp32
  * matrix instruction.  workspace: fpq_rl_workspace_size bytes, 256-byte aligned, no initialisation. */
+/* A convolution takes part as the linear layer on its patch matrix (the paper: "can be applied to other
+ * layers such as Convolutional"): fpq_rl_im2col writes, for x NCHW [B, C, H, W] fp32, the matrix
+ * a[B * Ho * Wo, C * kh * kw] whose row (b, ho, wo) is the receptive field of that output pixel in the
+ * order of the flattened weight [Cout, (ci, kh, kw)], zero where it reaches into the padding; w[N, K] is
+ * then the weight tensor as it stands, K = C * kh * kw, and the learned mask has the weight's shape. */
+int fpq_rl_im2col(const float *x, int64_t B, int64_t C, int64_t H, int64_t W, int kh, int kw, int stride,
+                  int pad, float *a, void *stream);
 size_t fpq_rl_workspace_size(int64_t M, int64_t N, int64_t K);
 int fpq_rl_init_alpha(const float *w, const float *sw, int64_t N, int64_t K, fpq_format_t f, float *alpha,
                       void *stream);

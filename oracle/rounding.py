@@ -94,3 +94,19 @@ def init_alpha(W, sw, fmt, eps=1e-3):
 def mask(alpha):
     """The decision used at inference: 1 (round up) where sigmoid(alpha) >= 0.5."""
     return (sigmoid(alpha) >= 0.5).astype(np.uint8)
+
+
+def im2col(x, kh, kw, stride, pad):
+    """Patch matrix of a convolution input x [B, C, H, W]: row (b, ho, wo), column (ci, r, c) = x[b, ci, ho stride - pad + r,
+    wo stride - pad + c], zero outside the image: a convolution with weight [Cout, C, kh, kw] is the linear layer with the
+    weight flattened to [Cout, C kh kw] on this matrix."""
+    x = np.asarray(x, dtype=np.float64)
+    B, C, H, W = x.shape
+    Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+    xp = np.zeros((B, C, H + 2 * pad, W + 2 * pad))
+    xp[:, :, pad:pad + H, pad:pad + W] = x
+    a = np.zeros((B, Ho, Wo, C, kh, kw))
+    for r in range(kh):
+        for c in range(kw):
+            a[:, :, :, :, r, c] = xp[:, :, r:r + stride * Ho:stride, c:c + stride * Wo:stride].transpose(0, 2, 3, 1)
+    return a.reshape(B * Ho * Wo, C * kh * kw)

@@ -97,6 +97,8 @@ def lib():
     L.fpq_rl_init_alpha.argtypes = [f32p, f32p, i64, i64, F, f32p, vp]
     L.fpq_rl_step.restype = i32
     L.fpq_rl_step.argtypes = [f32p, f32p, i64, i64, F, f32p, f32p, i64, fl, fl, f32p, f32p, vp, sz, vp]
+    L.fpq_rl_im2col.restype = i32
+    L.fpq_rl_im2col.argtypes = [f32p, i64, i64, i64, i64, i32, i32, i32, i32, f32p, vp]
     L.fpq_rl_mask.restype = i32
     L.fpq_rl_mask.argtypes = [f32p, sz, u8p, vp]
     L.fpq_count_zeros_workspace_size.restype = sz
@@ -112,7 +114,7 @@ EXPORTS = ["fpq_strerror", "fpq_format_max", "fpq_format_check", "fpq_bias_to_sc
            "fpq_dequantize", "fpq_packed_size", "fpq_pack_weights", "fpq_gemm_workspace_size", "fpq_gemm",
            "fpq_conv2d_workspace_size", "fpq_conv2d", "fpq_search_workspace_size", "fpq_search_format",
            "fpq_count_zeros_workspace_size", "fpq_count_zeros", "fpq_gemm_codes_out", "fpq_conv2d_codes_out",
-           "fpq_rl_workspace_size", "fpq_rl_init_alpha", "fpq_rl_step", "fpq_rl_mask", "fpq_packed_check"]
+           "fpq_rl_workspace_size", "fpq_rl_init_alpha", "fpq_rl_step", "fpq_rl_mask", "fpq_packed_check", "fpq_rl_im2col"]
 
 
 def fmt(f):
@@ -297,3 +299,8 @@ def fpq_rl_mask(alpha, mask):
 def fpq_packed_check(packed, N, Cin, kh, kw, f):
     """Status code (0 = the buffer was packed for these arguments); synchronises the current stream."""
     return lib().fpq_packed_check(_ptr(packed), N, Cin, kh, kw, fmt(f), _stream())
+
+
+def fpq_rl_im2col(x, kh, kw, stride, pad, a):
+    B_, C_, H, W = x.shape
+    _check(lib().fpq_rl_im2col(_ptr(x), B_, C_, H, W, kh, kw, stride, pad, _ptr(a), _stream()), "fpq_rl_im2col")

@@ -194,6 +194,15 @@ int fpq_rl_init_alpha(const float* w, const float* sw, int64_t N, int64_t K, fpq
     return launch_rl_init(w, sw, N, K, q, alpha, static_cast<hipStream_t>(stream));
 }
 
+int fpq_rl_im2col(const float* x, int64_t B, int64_t C, int64_t H, int64_t W, int kh, int kw, int stride, int pad, float* a,
+                  void* stream)
+{
+    if (B <= 0 || C <= 0 || H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0) return FPQ_ERR_SHAPE;
+    if (H + 2 * pad < kh || W + 2 * pad < kw || kh > 64 || kw > 64 || C * kh * kw >= (int64_t)1 << 24) return FPQ_ERR_SHAPE;
+    if (!x || !a) return FPQ_ERR_NULL;
+    return launch_rl_im2col(x, B, C, H, W, kh, kw, stride, pad, a, static_cast<hipStream_t>(stream));
+}
+
 int fpq_rl_mask(const float* alpha, size_t n, uint8_t* mask, void* stream)
 {
     if (n && (!alpha || !mask)) return FPQ_ERR_NULL;

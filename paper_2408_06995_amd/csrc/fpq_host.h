@@ -183,6 +183,8 @@ int launch_search(const float* x, size_t n, const SearchArgs& a, const float* ab
 size_t rl_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int launch_rl_init(const float* w, const float* sw, int64_t N, int64_t K, const QParams& q, float* alpha, hipStream_t st);
 int launch_rl_mask(const float* alpha, size_t n, uint8_t* mask, hipStream_t st);
+int launch_rl_im2col(const float* x, int64_t B, int64_t C, int64_t H, int64_t W, int kh, int kw, int stride, int pad,
+                     float* a, hipStream_t st);
 int launch_rl_step(const float* w, const float* sw, int64_t N, int64_t K, const QParams& q, float* alpha, const float* a,
                    int64_t M, float lr, float reg_weight, float* loss_out, float* grad_out, void* workspace, hipStream_t st);
 

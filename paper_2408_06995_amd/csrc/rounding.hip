@@ -145,6 +145,26 @@ __global__ __launch_bounds__(256) void rl_mask_kernel(const float* __restrict__ 
         mask[i] = alpha[i] >= 0.0f ? 1 : 0;                               // sigmoid(alpha) >= 0.5
 }
 
+// A convolution enters rounding learning as the linear layer on its patch matrix: row (b, ho, wo) of a holds the
+// receptive field of that output pixel in the order of the flattened weight [Cout, (ci, kh, kw)], zeros where the
+// field reaches into the padding.  Lanes run along the row (the kw taps of one (ci, kh) are neighbours in x).
+__global__ __launch_bounds__(256) void rl_im2col_kernel(const float* __restrict__ x, int C, int H, int W, int kh, int kw,
+                                                        int stride, int pad, int Ho, int Wo, size_t rows,
+                                                        float* __restrict__ a)
+{
+    const int K = C * kh * kw;
+    const size_t total = rows * (size_t)K;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const size_t row = i / K;
+        const int k = (int)(i - row * K);
+        const int ci = k / (kh * kw), t = k - ci * (kh * kw), r = t / kw, c = t - r * kw;
+        const int wo = (int)(row % Wo), ho = (int)((row / Wo) % Ho);
+        const size_t b = row / ((size_t)Wo * Ho);
+        const int h = ho * stride - pad + r, w = wo * stride - pad + c;
+        a[i] = (h >= 0 && h < H && w >= 0 && w < W) ? x[((b * C + ci) * H + h) * (size_t)W + w] : 0.0f;
+    }
+}
+
 // ---------------------------------------------------------------------------------- fp32 contraction
 //
 // C[i, j] = scale * sum_k P(i, k) Q(j, k), i < I, j < J, k < Kc, with P(i, k) = p[i * pi + k * pk] and the same for Q:
@@ -309,6 +329,19 @@ size_t rl_workspace_bytes(int64_t M, int64_t N, int64_t K)
     // D [N, K], R [M, N], 2 x 1024 partial sums, G [slices][N, K]
     auto up = [](size_t v) { return (v + 255) / 256 * 256; };
     return up((size_t)N * K * 4) + up((size_t)M * N * 4) + 2 * 4096 + up((size_t)rl_slices(M, N, K) * N * K * 4);
+}
+
+int launch_rl_im2col(const float* x, int64_t B, int64_t C, int64_t H, int64_t W, int kh, int kw, int stride, int pad,
+                     float* a, hipStream_t st)
+{
+    const int Ho = (int)((H + 2 * pad - kh) / stride + 1), Wo = (int)((W + 2 * pad - kw) / stride + 1);
+    const size_t rows = (size_t)B * Ho * Wo;
+    const size_t total = rows * (size_t)(C * kh * kw);
+    size_t grid = (total + 1023) / 1024;
+    if (grid > 8192) grid = 8192;
+    hipLaunchKernelGGL(rl_im2col_kernel, dim3((unsigned)grid), dim3(256), 0, st, x, (int)C, (int)H, (int)W, kh, kw, stride, pad,
+                       Ho, Wo, rows, a);
+    return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
 }
 
 int launch_rl_init(const float* w, const float* sw, int64_t N, int64_t K, const QParams& q, float* alpha, hipStream_t st)

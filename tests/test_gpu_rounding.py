@@ -129,6 +129,36 @@ def test_learning_run_follows_the_oracle_and_feeds_pack_weights():
     assert out_err(wq) <= out_err(near) * 1.05
 
 
+@pytest.mark.parametrize("case", [(2, 5, 9, 7, 3, 1, 1), (1, 16, 12, 12, 3, 2, 1), (3, 4, 6, 6, 1, 1, 0), (1, 3, 11, 8, 5, 1, 2)])
+def test_patch_matrix_exact_and_conv_step(case):
+    """The patch matrix is a copy (exact); a rounding-learning step of a convolution = the linear step on it."""
+    Bn, C, H, W, k, stride, pad = case
+    x = synth.activations((Bn, C, H, W), 9800 + C)
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    M, K = Bn * Ho * Wo, C * k * k
+    a = torch.full((M, K), float("nan"), device=DEV)
+    B.fpq_rl_im2col(dev(x), k, k, stride, pad, a)
+    torch.cuda.synchronize()
+    A = R.im2col(x, k, k, stride, pad)
+    assert np.array_equal(a.cpu().numpy().astype(np.float64), A)
+    fmt = E2M1
+    N = 6
+    Wt = synth.weights((N, C, k, k), 9850).reshape(N, K)
+    sw = (np.abs(Wt).max(axis=1) / np.float32(fmt[3])).astype(np.float32)
+    alpha = R.init_alpha(Wt, sw, fmt).astype(np.float32)
+    al = dev(alpha.copy())
+    loss = torch.zeros(2, device=DEV)
+    grad = torch.zeros((N, K), device=DEV)
+    ws = torch.empty(B.fpq_rl_workspace_size(M, N, K), dtype=torch.uint8, device=DEV)
+    B.fpq_rl_step(dev(Wt), dev(sw), fmt, al, a, 10.0, 0.1, loss, grad, ws)
+    torch.cuda.synchronize()
+    mse, reg = R.loss(Wt, sw, alpha, A.astype(np.float32), fmt, 0.1)
+    g = R.gradient(Wt, sw, alpha, A.astype(np.float32), fmt, 0.1)
+    assert loss.cpu().numpy()[0] == pytest.approx(mse, rel=1e-3, abs=1e-12)
+    assert loss.cpu().numpy()[1] == pytest.approx(reg, rel=1e-4)
+    assert np.allclose(grad.cpu().numpy(), g, rtol=1e-3, atol=1e-6 * np.abs(g).max() + 1e-12)
+
+
 def test_argument_checks():
     import ctypes as C
     L = B.lib()

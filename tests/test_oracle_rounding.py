@@ -109,3 +109,17 @@ def test_descent_lowers_the_loss_and_sharpens_the_decisions():
     l1 = R.loss(W, sw, alpha, A, fmt, 0.01)
     assert l1[0] + 0.01 * l1[1] < l0[0] + 0.01 * l0[1]
     assert l1[1] < l0[1]
+
+
+@pytest.mark.parametrize("k,stride,pad", [(3, 1, 1), (3, 2, 1), (1, 1, 0), (5, 1, 2), (3, 1, 0)])
+def test_patch_matrix_turns_a_convolution_into_the_linear_layer(k, stride, pad):
+    """Against torch's unfold (a library routine) and against the convolution itself: A W^T = conv(x, W)."""
+    import torch
+    rng = np.random.default_rng(k * 10 + stride)
+    x = rng.normal(0, 1, (2, 5, 9, 7))
+    w = rng.normal(0, 1, (4, 5, k, k))
+    A = R.im2col(x, k, k, stride, pad)
+    unf = torch.nn.functional.unfold(torch.from_numpy(x), (k, k), padding=pad, stride=stride)     # [B, C k k, L]
+    assert np.array_equal(A, unf.permute(0, 2, 1).reshape(-1, 5 * k * k).numpy())
+    y = torch.nn.functional.conv2d(torch.from_numpy(x), torch.from_numpy(w), stride=stride, padding=pad).numpy()
+    assert np.allclose(A @ w.reshape(4, -1).T, y.transpose(0, 2, 3, 1).reshape(-1, 4), rtol=1e-12, atol=1e-12)
