@@ -403,6 +403,40 @@ def test_conv_one_hot_taps_exact():
         assert np.array_equal(y.cpu().numpy(), want)
 
 
+@pytest.mark.parametrize("kind", ["linear", "conv"])
+def test_dynamic_scale_of_an_all_zero_input(kind):
+    """absmax = 0: the scale is 1 (not 0 / c), every code is +0 and the result is the bias."""
+    fx, fw = synth.E4M3, synth.E2M1
+    if kind == "linear":
+        M, K, N = 300, 320, 160
+        w = synth.weights((N, K), 91)
+        x = torch.zeros((M, K), device=DEV)
+    else:
+        Bn, Cin, H, W, N = 2, 20, 9, 9, 33
+        w = synth.weights((N, Cin, 3, 3), 92)
+        x = torch.zeros((Bn, Cin, H, W), device=DEV)
+    packed, sw_t, _ = gpu_pack(w, fw, None, want_codes=False)
+    bias = np.linspace(-2, 2, N).astype(np.float32)
+    if kind == "linear":
+        y = torch.full((M, N), float("nan"), device=DEV)
+        ws = torch.full((B.fpq_gemm_workspace_size(M, N, K, 2),), 0xEE, dtype=torch.uint8, device=DEV)
+        B.fpq_gemm(x, B.FPQ_X_FP32_DYNAMIC, fx, 0.0, None, packed, fw, sw_t, dev(bias), y, M, N, K, B.FPQ_ACC_FP32, ws)
+        want = np.broadcast_to(bias, (M, N))
+        ncodes = M * K
+    else:
+        y = torch.full((Bn, N, H, W), float("nan"), device=DEV)
+        ws = torch.full((B.fpq_conv2d_workspace_size(Bn, Cin, H, W, N, 3, 3, 1, 1, 2),), 0xEE, dtype=torch.uint8, device=DEV)
+        B.fpq_conv2d(x, B.FPQ_X_FP32_DYNAMIC, fx, 0.0, None, packed, fw, sw_t, dev(bias), y, Bn, Cin, H, W, N, 3, 3, 1, 1,
+                     B.FPQ_ACC_FP32, ws)
+        want = np.broadcast_to(bias[None, :, None, None], (Bn, N, H, W))
+        ncodes = Bn * H * W * B.fpq_padded_channels(Cin)
+    torch.cuda.synchronize()
+    assert np.array_equal(y.cpu().numpy(), want)
+    h = ws.cpu().numpy()
+    assert np.all(h[:ncodes] == 0)
+    assert np.array_equal(h[-256:-248].view(np.float32), np.array([1.0, 0.0], dtype=np.float32))   # [scale, absmax]
+
+
 def test_packed_header_check():
     w = synth.weights((40, 24, 3, 3), 5)
     packed, _, _ = gpu_pack(w, synth.E2M1, None, want_codes=False)
