@@ -45,6 +45,10 @@ def parse():
     ap.add_argument("--acc", default="fp32", choices=["fp32", "fp8mfma"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the quantize-bandwidth probe and the other acc mode")
+    ap.add_argument("--per-class", metavar="FILE",
+                    help="also time every distinct layer shape of the workload on its own (layer kernel on prepared codes) "
+                         "and write a table to FILE: time, TFLOP/s, share of the MFMA peak, share of the roofline "
+                         "t_min = max(2MNK / peak, algorithmic bytes / 8 TB/s) and which term binds")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy (the known-size kernel that hardware-counter "
                          "readings of a profiler run are scaled by)")
@@ -261,6 +265,60 @@ def main():
                    "acc_mode": args.acc},
         "roofline": roofline,
     }
+
+    if args.per_class:
+        # one representative layer per distinct (kind, kernel, stride, M, K, N); 8 launches in a graph, 4 replays
+        seen, lines = {}, []
+        for s in states:
+            L = s.L
+            key = (L.kind, L.k if L.kind == "conv" else 1, L.stride if L.kind == "conv" else 1, L.M, L.K, L.N)
+            seen.setdefault(key, [s, 0])[1] += 1
+        peak_fl = (PEAK_BF16_TFLOPS if acc == B.FPQ_ACC_FP32 else PEAK_FP8_TFLOPS) * 1e12
+        lines.append("# per shape class of %s, accumulate mode %s: layer kernel alone on prepared codes" % (args.workload, args.acc))
+        lines.append("# t_min = max(2MNK / %.0f TFLOP/s, (activation codes + packed weights + fp32 output) / 8 TB/s)" % (peak_fl / 1e12))
+        lines.append("%-4s %-6s %1s %1s %6s %6s %6s %4s %9s %9s %7s %9s %6s" % (
+            "w", "kind", "k", "s", "M", "K", "N", "x", "us", "TFLOP/s", "%peak", "%roofline", "bound"))
+        tot_t, tot_min = 0.0, 0.0
+        for key, (s, cnt) in seen.items():
+            L = s.L
+            buf = codes_bufs.get(L.name)
+            if buf is None:
+                continue
+            for tag, fw in (("w8", FW8), ("w4", FW4)):
+                def one():
+                    if L.kind == "conv":
+                        B.fpq_conv2d(buf, 0, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, y, L.B, L.Cin, L.H, L.W,
+                                     L.Cout, L.k, L.k, L.stride, L.pad, acc, part_buf)
+                    else:
+                        B.fpq_gemm(buf, 0, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, y, L.M, L.N, L.K, acc,
+                                   part_buf)
+                one()
+                torch.cuda.synchronize()
+                gc = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gc):
+                    for _ in range(8):
+                        one()
+                gc.replay()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(4):
+                    gc.replay()
+                e1.record()
+                e1.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / 32
+                fl = synth.flops(L)
+                nbytes = buf.numel() + s.packed[tag].numel() + 4 * L.M * L.N
+                t_f, t_b = fl / peak_fl * 1e6, nbytes / (PEAK_HBM_GBS * 1e9) * 1e6
+                t_min = max(t_f, t_b)
+                lines.append("%-4s %-6s %1d %1d %6d %6d %6d %4d %9.1f %9.1f %7.1f %9.1f %6s" % (
+                    tag, L.kind, key[1], key[2], L.M, L.K, L.N, cnt, us, fl / us / 1e6, 100 * fl / (us * 1e-6) / peak_fl,
+                    100 * t_min / us, "mfma" if t_f >= t_b else "hbm"))
+                tot_t += us * cnt
+                tot_min += t_min * cnt
+        lines.append("# all layers of the step, each class weighted by its count: %.1f us against a roofline t_min of %.1f us (%.1f %%)"
+                     % (tot_t, tot_min, 100 * tot_min / tot_t))
+        with open(args.per_class, "w") as f:
+            f.write("\n".join(lines) + "\n")
 
     if not args.no_extras:
         # the same step with per-tensor scales calibrated beforehand (the paper finds them offline): the timed region
