@@ -180,6 +180,51 @@ def test_linear_activation_then_codes(M, K, N, fw, fy, acc, act):
         assert miss < 0.005
 
 
+def test_feed_forward_projection_at_full_size_sampled_rows():
+    """The transformer-block projection of configuration 3 (16384 x 320 -> 2560) as the U-Net runs it: gated GELU, then
+    codes for the output layer.  All of it runs on the GPU in the bench's launch configuration; the oracle computes
+    tile-corner and random rows one by one."""
+    M, K, N = 16384, 320, 2560
+    fx, fw, fy = E4M3, E2M1, E4M3
+    x = synth.activations((M, K), 3001)
+    w = synth.weights((N, K), 3501) * 4.0
+    h = synth.rounding_mask((N, K), 3751)
+    bias = np.linspace(-1, 1, N).astype(np.float32)
+    sx, xq, wq, sw = oracle_linear_inputs(x, w, h, fx, fw)
+    rng = np.random.default_rng(3)
+    rows = np.unique(np.concatenate([[0, 127, 128, 255, 256, M - 129, M - 128, M - 1], rng.integers(0, M, 120)]))
+    Y, T = oracle.gemm(xq, fx, sx, wq, fw, sw, bias, rows=rows)
+    t = 1e-5 * T + 1e-6
+    O = oracle.geglu(Y)
+    R = len(rows)
+    Yb, tb = Y.reshape(R, N // 32, 2, 16), t.reshape(R, N // 32, 2, 16)
+    a, g, ta, tg = Yb[:, :, 0, :], Yb[:, :, 1, :], tb[:, :, 0, :], tb[:, :, 1, :]
+    G = oracle.gelu(g)
+    dG = 1.13 * tg + 4e-7 * np.abs(g) + 1e-6 * np.abs(G) + 1e-12
+    tol = (np.abs(G) * ta + (np.abs(a) + ta) * dG + 1e-6 * np.abs(a * G)).reshape(R, N // 2)
+    sy = out_scale(O, fy)
+    packed, sw_t, _ = gpu_pack(w, fw, h, want_codes=False)
+    yq = torch.full((M, N // 2), 0xEE, dtype=torch.uint8, device=DEV)
+    ws = torch.empty(max(256, B.fpq_gemm_workspace_size(M, N, K, 0)), dtype=torch.uint8, device=DEV)
+    B.fpq_gemm_codes_out(dev(xq), 0, fx, sx, None, packed, fw, sw_t, dev(bias), fy, sy, None, yq, M, N, K,
+                         B.FPQ_ACC_FP32 | B.FPQ_ACT_GEGLU, ws)
+    torch.cuda.synchronize()
+    got = yq.cpu().numpy()
+    miss = check_codes_interval(got[rows], O, tol, fy, sy, "config-3 projection, gated, codes out")
+    assert miss < 0.005
+    # and the codes feed the output layer (1280 -> 320) as they stand
+    N2 = 320
+    w2 = synth.weights((N2, N // 2), 3502)
+    wq2, sw2 = oracle.pack_weights(w2, E4M3, None)
+    packed2, sw2_t, _ = gpu_pack(w2, E4M3, None, want_codes=False)
+    y2 = torch.full((M, N2), float("nan"), device=DEV)
+    ws2 = torch.empty(max(256, B.fpq_gemm_workspace_size(M, N2, N // 2, 0)), dtype=torch.uint8, device=DEV)
+    B.fpq_gemm(yq, 0, fy, sy, None, packed2, E4M3, sw2_t, None, y2, M, N2, N // 2, B.FPQ_ACC_FP32, ws2)
+    torch.cuda.synchronize()
+    Y2, T2 = oracle.gemm(got, fy, sy, wq2, E4M3, sw2, None, rows=rows)
+    assert np.all(np.abs(y2.cpu().numpy()[rows] - Y2) <= 1e-5 * T2 + 1e-6)
+
+
 @pytest.mark.parametrize("case", [(2, 32, 5, 5, 64, 1, 1, 0), (1, 48, 12, 10, 130, 3, 1, 0), (2, 64, 65, 63, 160, 3, 2, 1),
                                   (1, 640, 16, 16, 160, 3, 1, 1)])
 def test_conv_silu_then_codes(case):
