@@ -109,8 +109,8 @@ struct GemmPlan {
 // of which two workgroups fit on a compute unit.  When the tile grid alone would leave compute units
 // idle and K is deep, K is cut into slices (each split costs a reduction launch and a round trip of
 // the partial sums, which only a deep K pays back): 2 to 4 slices of the 256-row tile when that gives
-// about one work item per compute unit with at least 32 K steps each, otherwise about two work items
-// per compute unit of the 128-row tile with at least 8 K steps each.  Problems of a few tiles and a
+// about one work item per compute unit with at least 32 K steps each, otherwise one work item per compute
+// unit of the 128-row tile (two when each keeps 20 K steps), with at least 8 K steps each.  Problems of a few tiles and a
 // short K are bound by the length of their serial K loop and are sliced as well.  At most 256 MB of
 // partial sums.
 static inline GemmPlan plan_gemm(int64_t M, int64_t N, int64_t Kpad)
@@ -143,7 +143,8 @@ static inline GemmPlan plan_gemm(int64_t M, int64_t N, int64_t Kpad)
         p.tile = TILE_256x160_S3;
         s = (256 + tiles256 / 2) / tiles256;
     } else if (tiles < 192 && nk >= 16) {
-        s = (512 + tiles / 2) / tiles;
+        s = (256 + tiles - 1) / tiles;              // one work item per compute unit ...
+        if (nk / (2 * s) >= 20) s *= 2;             // ... two when each still has 20 K steps
         if (s > nk / 8) s = nk / 8;
         if (s > 32) s = 32;
     } else if (tiles <= 16 && nk >= 4) {
