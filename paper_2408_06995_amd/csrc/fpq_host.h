@@ -127,6 +127,7 @@ static inline GemmPlan plan_gemm(int64_t M, int64_t N, int64_t Kpad)
         return p;
     }
 #endif
+    if (M <= 16) return p;   // at most 16 rows: the register-staged kernels (linear layers: one that splits K over its waves)
     const int64_t nk = Kpad / 128;
     // Small outputs with a short K: the register-staged kernel with its 64 x 64 tiles spreads them over more
     // workgroups and has a shorter serial K loop (M = 616, K = 768: 6.5 us against 12 us).

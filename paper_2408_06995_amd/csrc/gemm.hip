@@ -424,9 +424,93 @@ static int launch_conv_or_linear(const GemmArgs& a, hipStream_t st)
     return a.conv_out ? launch_tiles<XKIND, WKIND, ACC, true>(a, st) : launch_tiles<XKIND, WKIND, ACC, false>(a, st);
 }
 
+// ---------------------------------------------------------------------------------- M <= 16
+//
+// Linear layers with at most 16 rows (the time-embedding projections of the U-Net: M = batch).  The work is a few
+// MFLOP; what counts is the length of the dependent chain.  A workgroup owns 16 output columns; its four wavefronts
+// split K in steps of 64 codes (two 16x16x32 bf16 MFMAs per step: A = the rows of x, padded to 16 with zeros, B = 16
+// weight rows), keep up to five steps of loads in flight each, and add their partial blocks through LDS.
+// Hardware E4M3 activations with E4M3 or E2M1 weights, fp32 accumulate, fp32 result.
+typedef float v4f_t __attribute__((ext_vector_type(4)));
+
+template <int WKIND>
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(const GemmArgs a)
+{
+    constexpr bool W4 = kind_is_4bit(WKIND);
+    constexpr int U = 5;    // K = 1280, the width of the embedding layers, is one round of loads per wave
+    __shared__ float red[3][64][4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r16 = lane & 15, kq = lane >> 4;        // row of x / weight row within the block; the lane's quarter of a step
+    const int n0 = blockIdx.x * 16;
+    const int K = a.Kreal;                            // codes per row of x (a multiple of 16)
+    const int nsteps = (K + 63) / 64;                 // a step = 64 codes = two MFMAs
+    const bool has_m = r16 < a.M, has_n = n0 + r16 < a.N;
+    const uint8_t* xrow = a.x + (size_t)(has_m ? r16 : 0) * K;
+    const uint8_t* wrow = a.wrows + (size_t)(has_n ? n0 + r16 : 0) * (W4 ? a.Kpad / 2 : a.Kpad);
+    const GenFmt nofmt{0, 0, 0};
+    v4f_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    // Which k a lane feeds to which MFMA is free as long as both operands agree: the lane takes the 16 consecutive
+    // codes 64 s + 16 kq .. + 15 of its row in one load (the four lanes of a row read 64 contiguous bytes), the
+    // first eight go to the step's first MFMA, the other eight to its second.
+    for (int s0 = wave; s0 < nsteps; s0 += 4 * U) {
+        uint4 xv[U], wv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int k = 64 * (s0 + 4 * u) + 16 * kq;         // K % 16 == 0: the 16 codes lie inside the row or outside
+            const bool in = s0 + 4 * u < nsteps && k < K;
+            xv[u] = (in && has_m) ? *reinterpret_cast<const uint4*>(xrow + k) : make_uint4(0u, 0u, 0u, 0u);
+            if (W4) {
+                const uint2 t = (in && has_n) ? *reinterpret_cast<const uint2*>(wrow + k / 2) : make_uint2(0u, 0u);
+                wv[u] = make_uint4(t.x, 0u, t.y, 0u);
+            } else {
+                wv[u] = (in && has_n) ? *reinterpret_cast<const uint4*>(wrow + k) : make_uint4(0u, 0u, 0u, 0u);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(decode8<OPK_FP8>(xv[u].x, xv[u].y, nofmt),
+                                                          decode8<WKIND>(wv[u].x, wv[u].y, nofmt), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(decode8<OPK_FP8>(xv[u].z, xv[u].w, nofmt),
+                                                          decode8<WKIND>(wv[u].z, wv[u].w, nofmt), acc, 0, 0, 0);
+        }
+    }
+    if (wave > 0) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[wave - 1][lane][r] = acc[r];
+    }
+    __syncthreads();
+    if (wave == 0) {
+        // acc[r]: row 4 (lane / 16) + r of x, column lane % 16 of the block
+        const int n = n0 + r16;
+        if (n < a.N) {
+            const float sc = (a.sx_dev ? a.sx_dev[0] : a.sx) * a.alpha * a.sw[n];
+            const float bv = a.bias ? a.bias[n] : 0.0f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int m = 4 * kq + r;
+                if (m < a.M) a.y[(size_t)m * a.N + n] = (acc[r] + red[0][lane][r] + red[1][lane][r] + red[2][lane][r]) * sc + bv;
+            }
+        }
+    }
+}
+
+static bool skinny_applicable(const GemmArgs& a)
+{
+    return !a.conv_out && a.M <= 16 && a.acc_mode == FPQ_ACC_FP32 && a.xkind == OPK_FP8 &&
+           (a.wkind == OPK_FP8 || a.wkind == OPK_FP4) && !a.yq && !a.accumulate && a.splits == 1;
+}
+
 int launch_gemm(const GemmArgs& a, hipStream_t st)
 {
     if (a.M <= 0 || a.N <= 0) return FPQ_OK;
+    if (skinny_applicable(a)) {
+        const dim3 grid((unsigned)((a.N + 15) / 16));
+        if (a.wkind == OPK_FP8)
+            hipLaunchKernelGGL(gemm_skinny_kernel<OPK_FP8>, grid, dim3(256), 0, st, a);
+        else
+            hipLaunchKernelGGL(gemm_skinny_kernel<OPK_FP4>, grid, dim3(256), 0, st, a);
+        return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
+    }
     if (gemm_dma_applicable(a)) return launch_gemm_dma(a, st);
     if (a.splits > 1) return FPQ_ERR_UNSUPPORTED;   // plan_gemm only splits for the large-tile kernels
     if (a.acc_mode == FPQ_ACC_FP8_MFMA) {

@@ -437,6 +437,23 @@ def test_dynamic_scale_of_an_all_zero_input(kind):
     assert np.array_equal(h[-256:-248].view(np.float32), np.array([1.0, 0.0], dtype=np.float32))   # [scale, absmax]
 
 
+@pytest.mark.parametrize("M,K,N", [(8, 1280, 1280), (8, 320, 1280), (16, 5120, 320), (1, 16, 1), (3, 48, 17), (13, 2576, 100),
+                                     (16, 32, 16), (7, 8192, 33)])
+@pytest.mark.parametrize("fwn", ["E4M3", "E2M1"])
+def test_linear_with_at_most_sixteen_rows(M, K, N, fwn):
+    """The kernel that splits K over the waves of a workgroup: ragged N, K not a multiple of 32, a K deep enough for
+    several rounds of loads, bias, fp32 and codes input."""
+    fx, fw = resolved(FORMATS["E4M3"]), resolved(FORMATS[fwn])
+    x = synth.activations((M, K), 8000 + M + K)
+    w = synth.weights((N, K), 8500 + N)
+    h = synth.rounding_mask((N, K), 8750 + N) if fwn == "E2M1" else None
+    bias = np.linspace(-1, 1, N).astype(np.float32)
+    for fp32_in in (False, True):
+        y, (sx, xq, wq, sw) = run_linear(x, w, h, fx, fw, B.FPQ_ACC_FP32, bias, fp32_in=fp32_in)
+        Y, T = oracle.gemm(xq, fx, sx, wq, fw, sw, bias)
+        check_close(y, Y, T, what="skinny linear %s" % ((M, K, N, fwn, fp32_in),))
+
+
 def test_packed_header_check():
     w = synth.weights((40, 24, 3, 3), 5)
     packed, _, _ = gpu_pack(w, synth.E2M1, None, want_codes=False)
