@@ -471,7 +471,19 @@ static int run_layer(const CodesOut* out, const void* x, int x_is_fp32, fpq_form
         if (reinterpret_cast<uintptr_t>(x) & 3) return FPQ_ERR_ALIGN;
         uint8_t* buf = static_cast<uint8_t*>(workspace);
         ScaleSrc ss{sx, sx_dev, nullptr, 0, 0.0f, nullptr};
-        if (dyn) {
+        bool quantized = false;
+        if (dyn && !conv_out && Cp == Cin) {
+            // a tensor of a few thousand elements: maximum, scale and codes by one workgroup in one launch
+            float* dynbuf = reinterpret_cast<float*>(buf + codes_bytes + part_bytes);
+            st = launch_quantize_dynamic_small(static_cast<const float*>(x), (size_t)M * Cin, qx, qx.c, dynbuf + 1024, buf, s);
+            if (st == FPQ_OK) {
+                quantized = true;
+                sx_dev = dynbuf + 1024;
+            } else if (st != FPQ_ERR_UNSUPPORTED) {
+                return st;
+            }
+        }
+        if (dyn && !quantized) {
             // per-tensor scale = absmax(x) / maxval found here: one reduction launch leaves per-block maxima,
             // the quantize kernel folds them and publishes the scale the layer kernel reads
             float* dynbuf = reinterpret_cast<float*>(buf + codes_bytes + part_bytes);
@@ -484,7 +496,9 @@ static int run_layer(const CodesOut* out, const void* x, int x_is_fp32, fpq_form
             ss.publish = dynbuf + 1024;
             sx_dev = dynbuf + 1024;
         }
-        if (conv_out) {
+        if (quantized) {
+            st = FPQ_OK;
+        } else if (conv_out) {
             st = launch_quantize_nhwc(static_cast<const float*>(x), B, Cin, H, W, qx, ss, buf, s);
         } else if (Cp == Cin) {
             st = launch_quantize(static_cast<const float*>(x), (size_t)M * Cin, qx, false, ss, buf, s);

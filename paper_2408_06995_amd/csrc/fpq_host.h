@@ -201,6 +201,8 @@ int launch_count_zeros(const void* x, int is_fp32, size_t n, int em, bool four_b
 int launch_absmax(const float* x, size_t n, float maxval, float* absmax_out, float* scale_out, float* partial,
                   hipStream_t st);
 int launch_absmax_partials(const float* x, size_t n, float* partial, hipStream_t st);
+int launch_quantize_dynamic_small(const float* x, size_t n, const QParams& q, float maxval, float* publish, uint8_t* codes,
+                                  hipStream_t st);
 int launch_quantize(const float* x, size_t n, const QParams& q, bool four_bit, const ScaleSrc& ss, uint8_t* codes,
                     hipStream_t st);
 int launch_quantize_nhwc(const float* x, int64_t B, int64_t C, int64_t H, int64_t W, const QParams& q,

@@ -282,6 +282,50 @@ int launch_quantize(const float* x, size_t n, const QParams& q, bool four_bit, c
     return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
 }
 
+// Dynamic per-tensor scale of a tensor so small that one workgroup holds it in registers (up to 16 Ki elements: the
+// time-embedding vectors of the U-Net): all loads in flight at once (sixteen 16-byte loads per lane at most), maximum
+// of |x|, scale, and the codes from the registers, in one launch.  Bit-identical to the two-launch form.
+__global__ __launch_bounds__(256) void quantize_dynamic_small_kernel(const float4* __restrict__ x4, int n4, QParams q,
+                                                                     float maxval, float* __restrict__ publish,
+                                                                     uint8_t* __restrict__ codes)
+{
+    float4 v[16];
+    float m = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const int i = e * 256 + threadIdx.x;
+        v[e] = i < n4 ? x4[i] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        m = max4(m, v[e]);
+    }
+    m = block_max(m);
+    const float sc = (m == 0.0f) ? 1.0f : __fdiv_rn(m, maxval);
+    if (threadIdx.x == 0) {
+        publish[0] = sc;
+        publish[1] = m;
+    }
+    const float r = __fdiv_rn(1.0f, sc);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const int i = e * 256 + threadIdx.x;
+        if (i < n4) {
+            const uint32_t c0 = quantize_nearest(v[e].x, r, q), c1 = quantize_nearest(v[e].y, r, q);
+            const uint32_t c2 = quantize_nearest(v[e].z, r, q), c3 = quantize_nearest(v[e].w, r, q);
+            reinterpret_cast<uint32_t*>(codes)[i] = c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+        }
+    }
+}
+
+// FPQ_OK when the one-launch form ran, FPQ_ERR_UNSUPPORTED when it does not apply (size, alignment).
+int launch_quantize_dynamic_small(const float* x, size_t n, const QParams& q, float maxval, float* publish, uint8_t* codes,
+                                  hipStream_t st)
+{
+    if (n == 0 || n > 16384 || (n & 3) || (reinterpret_cast<uintptr_t>(x) & 15) || (reinterpret_cast<uintptr_t>(codes) & 3))
+        return FPQ_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(quantize_dynamic_small_kernel, dim3(1), dim3(256), 0, st, reinterpret_cast<const float4*>(x),
+                       (int)(n >> 2), q, maxval, publish, codes);
+    return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
+}
+
 // ------------------------------------------------------------------- quantize NCHW -> NHWC codes
 
 // One block turns a 64-channel x 64-pixel patch of one image: reads run along pixels (contiguous in

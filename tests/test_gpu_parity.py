@@ -329,6 +329,7 @@ def test_conv_fp32_input_equals_codes_input():
 
 
 @pytest.mark.parametrize("shape", [("linear", 256, 320, 320), ("linear", 9, 40, 17), ("linear", 2048, 1280, 320),
+                                   ("linear", 8, 1280, 1280), ("linear", 16, 1024, 64), ("linear", 5, 48, 3), ("linear", 17, 1024, 64),
                                    ("conv", 2, 20, 9, 9, 24, 3, 1), ("conv", 1, 320, 32, 32, 320, 3, 1),
                                    ("conv", 2, 64, 16, 16, 160, 1, 2)])
 def test_dynamic_scale_entry_equals_absmax_then_quantize(shape):
@@ -403,12 +404,12 @@ def test_conv_one_hot_taps_exact():
         assert np.array_equal(y.cpu().numpy(), want)
 
 
-@pytest.mark.parametrize("kind", ["linear", "conv"])
-def test_dynamic_scale_of_an_all_zero_input(kind):
+@pytest.mark.parametrize("kind,small", [("linear", False), ("linear", True), ("conv", False)])
+def test_dynamic_scale_of_an_all_zero_input(kind, small):
     """absmax = 0: the scale is 1 (not 0 / c), every code is +0 and the result is the bias."""
     fx, fw = synth.E4M3, synth.E2M1
     if kind == "linear":
-        M, K, N = 300, 320, 160
+        M, K, N = (300, 320, 160) if small is False else (8, 320, 160)
         w = synth.weights((N, K), 91)
         x = torch.zeros((M, K), device=DEV)
     else:
