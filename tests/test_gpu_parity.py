@@ -455,6 +455,33 @@ def test_linear_with_at_most_sixteen_rows(M, K, N, fwn):
         check_close(y, Y, T, what="skinny linear %s" % ((M, K, N, fwn, fp32_in),))
 
 
+@pytest.mark.parametrize("case", [("linear", 616, 768, 320), ("linear", 616, 768, 1280), ("linear", 512, 1280, 1280),
+                                  ("linear", 33, 16, 31), ("linear", 100, 2560, 70), ("linear", 65, 1296, 97),
+                                  ("conv", 8, 1280, 8, 8, 1280), ("conv", 3, 48, 5, 7, 33), ("conv", 2, 2560, 8, 8, 160)])
+@pytest.mark.parametrize("fwn", ["E4M3", "E2M1"])
+def test_small_outputs_with_short_k(case, fwn):
+    """Small outputs with a short K, the shapes the plan sends to the register-staged kernels: the conditioning
+    projections (M = 616), the layers of the 8 x 8 stage (M = 512), 1 x 1 convolutions, ragged M / N, odd K."""
+    fx, fw = resolved(FORMATS["E4M3"]), resolved(FORMATS[fwn])
+    if case[0] == "linear":
+        _, M, K, N = case
+        x = synth.activations((M, K), 8100 + M)
+        w = synth.weights((N, K), 8600 + N)
+        h = synth.rounding_mask((N, K), 8850 + N) if fwn == "E2M1" else None
+        bias = np.linspace(-1, 1, N).astype(np.float32)
+        y, (sx, xq, wq, sw) = run_linear(x, w, h, fx, fw, B.FPQ_ACC_FP32, bias)
+        Y, T = oracle.gemm(xq, fx, sx, wq, fw, sw, bias)
+    else:
+        _, Bn, Cin, H, W, Cout = case
+        x = synth.activations((Bn, Cin, H, W), 8200 + Cin)
+        w = synth.weights((Cout, Cin, 1, 1), 8700 + Cout)
+        h = synth.rounding_mask(w.shape, 8950 + Cout) if fwn == "E2M1" else None
+        bias = np.linspace(-0.5, 0.5, Cout).astype(np.float32)
+        y, (sx, xq, wq, sw) = run_conv(x, w, h, fx, fw, 1, 0, B.FPQ_ACC_FP32, bias)
+        Y, T = oracle.conv2d(xq, fx, sx, wq, fw, sw, bias, stride=1, pad=0)
+    check_close(y, Y, T, what="small output, short K %s" % ((case, fwn),))
+
+
 def test_packed_header_check():
     w = synth.weights((40, 24, 3, 3), 5)
     packed, _, _ = gpu_pack(w, synth.E2M1, None, want_codes=False)
