@@ -31,9 +31,9 @@ PEAK_HBM_GBS = 8000.0
 ALU_LANE_RATE = 256 * 4 * 16 * 2.4e9   # vector instructions per lane and second: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
 SEARCH_OPS = 11                        # vector instructions per element and candidate in the search kernel's inner loop
 # HBM-side bytes per layer launch from the two hardware-counter passes whose summary is
-# profiles/cfg5_step_hbm_traffic_pmc.txt (30.43 MB fetched + 34.65 MB written, the split-K reductions included); a profiler figure, not
+# profiles/cfg5_step_hbm_traffic_pmc.txt (30.50 MB fetched + 36.39 MB written, the split-K reductions included); a profiler figure, not
 # measurable from inside this script, hence only for the workload and mode it was taken on.
-MEASURED_TRAFFIC = {("cfg5", "fp32"): 65.08e6}
+MEASURED_TRAFFIC = {("cfg5", "fp32"): 66.90e6}
 
 
 def parse():
@@ -49,6 +49,9 @@ def parse():
                     help="also time every distinct layer shape of the workload on its own (layer kernel on prepared codes) "
                          "and write a table to FILE: time, TFLOP/s, share of the MFMA peak, share of the roofline "
                          "t_min = max(2MNK / peak, algorithmic bytes / 8 TB/s) and which term binds")
+    ap.add_argument("--eager", action="store_true",
+                    help="launch every step call by call instead of replaying a captured graph (for hardware-counter "
+                         "passes of a profiler, where timing does not matter and every dispatch is serialized anyway)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy (the known-size kernel that hardware-counter "
                          "readings of a profiler run are scaled by)")
@@ -159,6 +162,12 @@ def main():
         for _ in range(max(1, warmup)):
             step(acc_mode, static_scale)
         torch.cuda.synchronize()
+        if args.eager:
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                step(acc_mode, static_scale)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / steps
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             step(acc_mode, static_scale)
@@ -221,14 +230,18 @@ def main():
             prepare_codes()
         nlaunch = gemm_only(acc_mode)
         torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            gemm_only(acc_mode)
-        graph.replay()
+        if args.eager:
+            replay = lambda: gemm_only(acc_mode)
+        else:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                gemm_only(acc_mode)
+            replay = graph.replay
+        replay()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(reps):
-            graph.replay()
+            replay()
         e1.record()
         e1.synchronize()
         tot_ms = e0.elapsed_time(e1) / reps
