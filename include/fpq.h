@@ -79,7 +79,9 @@ typedef enum fpq_acc_mode { FPQ_ACC_FP32 = 0, FPQ_ACC_FP8_MFMA = 1 } fpq_acc_mod
  * FPQ_X_FP32: fp32 activations; the library quantizes them first with the given scale sx / sx_dev.
  * FPQ_X_FP32_DYNAMIC: fp32 activations and no scale: the library finds the per-tensor scale
  *   absmax(x) / maxval itself (what fpq_absmax computes, bit for bit) on the way; sx and sx_dev are
- *   ignored.  One launch fewer than fpq_absmax followed by FPQ_X_FP32. */
+ *   ignored.  One launch fewer than fpq_absmax followed by FPQ_X_FP32.
+ * FPQ_X_CODES_BYTE is a value of fpq_count_zeros' x_kind only (codes stored one per byte whatever the format);
+ *   the layer calls return FPQ_ERR_UNSUPPORTED for it. */
 typedef enum fpq_x_kind { FPQ_X_CODES = 0, FPQ_X_FP32 = 1, FPQ_X_FP32_DYNAMIC = 2, FPQ_X_CODES_BYTE = 3 } fpq_x_kind;
 
 const char *fpq_strerror(int status);

@@ -438,7 +438,7 @@ static int run_layer(const CodesOut* out, const void* x, int x_is_fp32, fpq_form
     const int64_t M = B * Ho * Wo;
     const int64_t Cp = padded_channels(Cin);
     if (M >= (int64_t)1 << 31 || B * H * W * Cp >= (int64_t)1 << 31 || M * Cout >= (int64_t)1 << 40 ||
-        Cout >= (int64_t)1 << 24)
+        Cout >= (int64_t)1 << 24 || Cin * kh * kw > (1 << 28))   // the last: what fpq_pack_weights accepts
         return FPQ_ERR_SHAPE;
     if (!x || !packed_w || !sw || (out ? !out->yq : !y)) return FPQ_ERR_NULL;
     QParams qy{0, 0, 0, 0.0f};

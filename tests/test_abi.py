@@ -117,6 +117,9 @@ def test_argument_validation_without_gpu():
     assert L.fpq_gemm(p, 0, f, 1.0, None, p, f, p, None, p, 0, 8, 32, 0, None, 0, None) == 0
     assert L.fpq_conv2d(p, 0, f, 1.0, None, p, f, p, None, p, 1, 16, 2, 2, 8, 3, 3, 1, 0, 0, None, 0, None) == -4
     assert L.fpq_conv2d(p, 0, f, 1.0, None, p, f, p, None, p, 1, 16, 8, 8, 8, 3, 3, 0, 1, 0, None, 0, None) == -4
+    # a contraction longer than fpq_pack_weights can have packed (2^28 codes per output channel)
+    assert L.fpq_conv2d(p, 0, f, 1.0, None, p, e2m1, p, None, p, 1, 1 << 20, 1, 1, 1, 48, 48, 1, 24, 0, None, 0, None) == -4
+    assert L.fpq_pack_weights(p, 1, 1 << 20, 48, 48, e2m1, None, None, p, 1 << 40, p, None, None) == -4
     # zero count: null, kind, format, workspace, alignment
     assert B.fpq_count_zeros_workspace_size(10 ** 9) == 8192
     assert L.fpq_count_zeros(p, 0, 100, f, None, p, 8192, None) == -1

@@ -511,6 +511,66 @@ def test_fp32_input_with_more_rows_than_a_grid_dimension_and_padded_k():
     assert np.array_equal(codes[:, :K], xq) and np.all(codes[:, K:] == 0)
 
 
+@pytest.mark.parametrize("N", [2080, 1928])
+def test_output_with_more_than_two_to_the_31_elements(N):
+    """M * N > 2^32 (a 17 GB fp32 result; N = 2080 runs the large-tile kernel, 1928 the small-tile one): element
+    offsets must be 64-bit everywhere.  Compared with the oracle on whole rows: the first and the last ones, the
+    rows either side of elements 2^30, 2^31 and 2^32, and random ones."""
+    M, K = 2230001, 16
+    fx = fw = synth.E4M3
+    x = synth.activations((M, K), 91)
+    w = synth.weights((N, K), 92)
+    bias = np.linspace(-1, 1, N).astype(np.float32)
+    sx = oracle.scale_from_absmax(oracle.absmax(x), fx[3])
+    wq, sw = oracle.pack_weights(w, fw, None)
+    packed, sw_t, _ = gpu_pack(w, fw, None, want_codes=False)
+    y = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    y.fill_(float("nan"))
+    ws = torch.empty(B.fpq_gemm_workspace_size(M, N, K, 1), dtype=torch.uint8, device=DEV)
+    assert 2 ** 32 // N + 1 < M
+    print("launch M=%d N=%d K=%d" % (M, N, K), flush=True)
+    B.fpq_gemm(dev(x), 1, fx, sx, None, packed, fw, sw_t, dev(bias), y, M, N, K, B.FPQ_ACC_FP32, ws)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(y).any())
+    r30, r31, r32 = 2 ** 30 // N, 2 ** 31 // N, 2 ** 32 // N
+    rows = sorted(set([0, 1, 127, 128, M - 130, M - 2, M - 1, r30 - 1, r30, r30 + 1, r31 - 1, r31, r31 + 1, r32 - 1, r32,
+                       r32 + 1] +
+                      list(np.random.default_rng(93).integers(0, M, 40))))
+    got = y[torch.tensor(rows, device=DEV)].cpu().numpy()
+    del y
+    Y, T = oracle.gemm(oracle.quantize(x[rows], fx, sx), fx, sx, wq, fw, sw, bias)
+    check_close(got, Y, T, what="rows of a %d x %d result" % (M, N))
+
+
+@pytest.mark.parametrize("Cout", [320, 328])
+def test_conv_output_with_more_than_two_to_the_32_elements(Cout):
+    """The same for the NCHW result of a convolution (B * Cout * Ho * Wo > 2^32; 320 channels run the large-tile
+    kernel, 328 the small-tile one): whole images compared, among them those that hold elements 2^31 and 2^32."""
+    Bn, Cin, H, W, k = 830, 4, 128, 128, 3
+    fx = fw = synth.E4M3
+    x = synth.activations((Bn, Cin, H, W), 94)
+    w = synth.weights((Cout, Cin, k, k), 95)
+    bias = np.linspace(-1, 1, Cout).astype(np.float32)
+    sx = oracle.scale_from_absmax(oracle.absmax(x), fx[3])
+    wq, sw = oracle.pack_weights(w, fw, None)
+    packed, sw_t, _ = gpu_pack(w, fw, None, want_codes=False)
+    per_image = Cout * H * W
+    assert Bn * per_image > 2 ** 32
+    y = torch.empty((Bn, Cout, H, W), dtype=torch.float32, device=DEV)
+    y.fill_(float("nan"))
+    ws = torch.empty(B.fpq_conv2d_workspace_size(Bn, Cin, H, W, Cout, k, k, 1, 1, 1), dtype=torch.uint8, device=DEV)
+    print("launch B=%d Cout=%d" % (Bn, Cout), flush=True)
+    B.fpq_conv2d(dev(x), 1, fx, sx, None, packed, fw, sw_t, dev(bias), y, Bn, Cin, H, W, Cout, k, k, 1, 1,
+                 B.FPQ_ACC_FP32, ws)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(y).any())
+    images = sorted({0, 2 ** 30 // per_image, 2 ** 31 // per_image, 2 ** 32 // per_image, Bn - 1})
+    got = y[torch.tensor(images, device=DEV)].cpu().numpy()
+    del y
+    Y, T = oracle.conv2d(oracle.quantize(x[images], fx, sx), fx, sx, wq, fw, sw, bias, stride=1, pad=1)
+    check_close(got, Y, T, what="images %s of a %d-image result" % (images, Bn))
+
+
 # ------------------------------------------------------------------------------ large-tile (N % 160 == 0) kernels
 
 @pytest.mark.parametrize("M,K,N", [(256, 128, 160), (257, 144, 160), (300, 2880, 320), (1000, 320, 480), (512, 6400, 160),
