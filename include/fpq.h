@@ -136,7 +136,7 @@ typedef struct fpq_search_result {
  * (device, may be NULL); result receives the first candidate with the smallest error in the order
  * of Algorithm 1 (encodings outer, biases inner; the printed initial value prev_mse = 0 is read as
  * +infinity).  An all-zero tensor is searched as if absmax were 1.  One read of x; errors are summed
- * in fp32 per wavefront and round and in fp64 across them.  workspace: fpq_search_workspace_size
+ * in fp32 within a workgroup (at most 1024 of them share the tensor) and in fp64 across workgroups.  workspace: fpq_search_workspace_size
  * bytes, 256-byte aligned. */
 size_t fpq_search_workspace_size(size_t n, int n_enc, int n_bias);
 int fpq_search_format(const float *x, size_t n, const int32_t *ebits, const int32_t *mbits, int n_enc,
