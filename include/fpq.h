@@ -158,7 +158,9 @@ int fpq_search_format(const float *x, size_t n, const int32_t *ebits, const int3
  * position between its two grid neighbours (kept inside [1e-3, 1 - 1e-3]), so that learning starts from
  * the unquantized weights.  fpq_rl_mask writes the decision used at inference, 1 where
  * sigmoid(alpha) >= 0.5: the mask that fpq_pack_weights takes.  All products are fp32 on the fp32
- * matrix instruction.  workspace: fpq_rl_workspace_size bytes, 256-byte aligned, no initialisation. */
+ * matrix instruction.  workspace: fpq_rl_workspace_size bytes, 256-byte aligned, no initialisation.
+ * Size limits (FPQ_ERR_SHAPE beyond them): N K < 2^31, M N < 2^31, M < 2^23; lr and reg_weight finite and
+ * >= 0 (FPQ_ERR_SCALE otherwise). */
 /* A convolution takes part as the linear layer on its patch matrix (the paper: "can be applied to other
  * layers such as Convolutional"): fpq_rl_im2col writes, for x NCHW [B, C, H, W] fp32, the matrix
  * a[B * Ho * Wo, C * kh * kw] whose row (b, ho, wo) is the receptive field of that output pixel in the
@@ -259,7 +261,9 @@ int fpq_gemm(const void *x, int x_is_fp32, fpq_format_t fx, float sx, const floa
  * K = Cin*kh*kw, N = Cout.  x: x_is_fp32 == 0: codes [B, H, W, Cp] from fpq_quantize_nhwc;
  * x_is_fp32 == 1 or 2 (fpq_x_kind): fp32 NCHW [B, Cin, H, W], quantized by the library first into
  * the workspace.
- * y: fp32 NCHW [B, Cout, Ho, Wo], Ho = (H + 2 pad - kh) / stride + 1. */
+ * y: fp32 NCHW [B, Cout, Ho, Wo], Ho = (H + 2 pad - kh) / stride + 1.
+ * Size limits of both layer calls (FPQ_ERR_SHAPE beyond them): M = B Ho Wo < 2^31, B H W Cp < 2^31 (Cp = Cin
+ * rounded up to 16), M Cout < 2^40, Cout < 2^24, Cin kh kw <= 2^28, kh, kw, pad <= 64, H, W <= 16000. */
 size_t fpq_conv2d_workspace_size(int64_t B, int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh,
                                  int kw, int stride, int pad, int x_is_fp32);
 int fpq_conv2d(const void *x, int x_is_fp32, fpq_format_t fx, float sx, const float *sx_dev,
