@@ -6,6 +6,8 @@
 #include <stdint.h>
 #include <stdlib.h>
 
+#include <atomic>
+
 #include "../../include/fpq.h"
 
 namespace fpq {
@@ -15,6 +17,19 @@ struct ScaleSrc;
 
 // Channels of a channels-last code buffer: C rounded up to a whole 16-byte chunk.
 static inline int64_t padded_channels(int64_t C) { return (C + 15) / 16 * 16; }
+
+// A kernel that uses more than 64 KB of dynamic LDS must be told so once per device; `done` is the launcher's
+// bit mask of the devices that have been (one static per kernel instantiation; setting it twice is harmless).
+static inline bool allow_dynamic_lds(const void* kernel, int bytes, std::atomic<uint64_t>& done)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    const uint64_t bit = dev < 64 ? (uint64_t)1 << dev : 0;
+    if (bit && (done.load(std::memory_order_relaxed) & bit)) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return false;
+    done.fetch_or(bit, std::memory_order_relaxed);
+    return true;
+}
 
 // Length of a packed weight row: taps * Cp rounded up to the 128-code K step of the kernels.
 static inline int64_t padded_k(int64_t Cin, int64_t taps) { return (taps * padded_channels(Cin) + 127) / 128 * 128; }

@@ -396,13 +396,8 @@ static int launch_one(const GemmArgs& a, hipStream_t st)
     const int tiles = ((a.M + BX - 1) / BX) * ((a.N + BW - 1) / BW);
     auto kern = gemm_kernel<BX, BW, WGX, WGW, XKIND, WKIND, ACC, CONV>;
     if (smem > 64 * 1024) {
-        static bool raised = false;   // per instantiation
-        if (!raised) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    smem) != hipSuccess)
-                return FPQ_ERR_LAUNCH;
-            raised = true;
-        }
+        static std::atomic<uint64_t> allowed{0};   // per instantiation
+        if (!allow_dynamic_lds(reinterpret_cast<const void*>(kern), smem, allowed)) return FPQ_ERR_LAUNCH;
     }
     hipLaunchKernelGGL(kern, dim3(tiles), dim3(256), smem, st, a);
     return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;

@@ -833,13 +833,8 @@ static int launch_dma_one(const GemmArgs& a, hipStream_t st)
     constexpr int smem = NSTAGE * (BX * 128 + (BW * WROWB + 4095) / 4096 * 4096) + 4096;   // ring + scale / bias slots
     const int tiles = ((a.M + BX - 1) / BX) * ((a.N + BW - 1) / BW);
     auto kern = gemm_dma_kernel<BX, BW, NSTAGE, XKIND, WKIND, ACC, CONV, QOUT>;
-    static bool raised = false;   // per instantiation
-    if (!raised) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
-            hipSuccess)
-            return FPQ_ERR_LAUNCH;
-        raised = true;
-    }
+    static std::atomic<uint64_t> allowed{0};   // per instantiation
+    if (!allow_dynamic_lds(reinterpret_cast<const void*>(kern), smem, allowed)) return FPQ_ERR_LAUNCH;
     const int nitems = tiles * a.splits;
     constexpr int max_wgs = (smem <= 80 * 1024) ? 512 : 256;   // resident workgroups: two per compute unit when the LDS allows
     hipLaunchKernelGGL(kern, dim3(nitems < max_wgs ? nitems : max_wgs), dim3(256), smem, st, a);
