@@ -47,7 +47,21 @@ SHAPES = [(3, 5, 6), (33, 70, 45), (130, 96, 200), (320, 320, 256), (640, 1280, 
 @pytest.mark.parametrize("N,K,M", SHAPES)
 @pytest.mark.parametrize("fmt", [E2M1, E4M3, E1M2])
 def test_step_against_oracle(N, K, M, fmt):
-    W, sw, A, alpha = layer(N, K, M, 9000 + N, fmt)
+    check_step(N, K, M, fmt, 9000 + N)
+
+
+@pytest.mark.parametrize("i", range(24))
+def test_step_on_random_shapes(i):
+    """Shapes drawn at random: every combination of ragged tiles of the two fp32 contractions and of their K slices."""
+    rng = np.random.default_rng(9500 + i)
+    N, K, M = int(rng.integers(1, 400)), int(rng.integers(1, 500)), int(rng.integers(1, 3000))
+    fmt = [E2M1, E4M3, E1M2, (3, 0, 4, 8.0)][i % 4]
+    print("case", i, (N, K, M), fmt, flush=True)
+    check_step(N, K, M, fmt, 9600 + i)
+
+
+def check_step(N, K, M, fmt, seed):
+    W, sw, A, alpha = layer(N, K, M, seed, fmt)
     lr, regw = 50.0, 0.3
     a1, loss, grad = gpu_step(W, sw, alpha, A, fmt, lr, regw)
     mse, reg = R.loss(W, sw, alpha, A, fmt, regw)
