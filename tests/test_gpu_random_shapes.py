@@ -146,3 +146,51 @@ def test_random_conv(i):
         B.fpq_conv2d(xarg, xin, fx, sx, None, packed, fw, sw_t, bias_t, y, Bn, Cin, H, W, Cout, k, k, stride, pad, c["acc"], ws)
         torch.cuda.synchronize()
         check_close(y.cpu().numpy(), Y, T, rel=rel, what=str(c))
+
+
+ALL_FORMATS = [E4M3, E5M2, E2M1, synth.E1M2, synth.E3M4, synth.E2M5, synth.E3M0, (4, 3, 7, 480.0), (4, 3, 9, 112.0),
+               (5, 2, 15, 0.0), (2, 1, 2, 3.0), (3, 2, 3, 28.0), (1, 6, 1, 0.0), (4, 3, -3, 0.0), (2, 3, 1, 0.875)]
+
+
+@pytest.mark.parametrize("i", range(40))
+def test_random_pack_weights(i):
+    """Weight codes and scales, bit for bit: random shape and format, with / without mask, computed or given scales."""
+    rng = np.random.default_rng(8500 + i)
+    f = resolved(ALL_FORMATS[int(rng.integers(0, len(ALL_FORMATS)))])
+    k = int(rng.choice([1, 1, 3, 5]))
+    shape = (int(rng.integers(1, 200)), int(rng.integers(1, 300)), k, k)
+    print("case", i, shape, f, flush=True)
+    w = synth.weights(shape, 8600 + i)
+    w.reshape(-1)[::int(rng.integers(2, 50))] = 0.0
+    if rng.random() < 0.3:
+        w[int(rng.integers(0, shape[0]))] = 0.0                       # an all-zero output channel
+    h = synth.rounding_mask(shape, 8700 + i) if rng.random() < 0.6 else None
+    sc = rng.uniform(0.001, 0.05, shape[0]).astype(np.float32) if rng.random() < 0.4 else None
+    want_codes, want_sw = oracle.pack_weights(w, f, h, sc)
+    _, sw, codes = gpu_pack(w, f, h, sc)
+    assert np.array_equal(sw.cpu().numpy(), want_sw)
+    assert np.array_equal(codes, want_codes), int((codes != want_codes).sum())
+
+
+@pytest.mark.parametrize("i", range(32))
+def test_random_quantize_nhwc(i):
+    """Channels-last activation codes with channel padding, bit for bit, static and device scale."""
+    rng = np.random.default_rng(8800 + i)
+    f = resolved([E4M3, E5M2, synth.E3M4, synth.E2M5, (4, 3, 7, 480.0)][int(rng.integers(0, 5))])
+    shape = (int(rng.integers(1, 5)), int(rng.integers(1, 200)), int(rng.integers(1, 40)), int(rng.integers(1, 40)))
+    print("case", i, shape, f, flush=True)
+    x = synth.activations(shape, 8900 + i)
+    sx = float(np.float32(oracle.scale_from_absmax(oracle.absmax(x), f[3]) * rng.uniform(0.5, 1.5)))
+    Bn, Cc, H, W = shape
+    Cp = B.fpq_padded_channels(Cc)
+    codes = torch.full((Bn * H * W * Cp + 16,), 0xEE, dtype=torch.uint8, device=DEV)
+    if i & 1:
+        B.fpq_quantize_nhwc(dev(x), f, 0.0, dev(np.array([sx], dtype=np.float32)), codes)
+    else:
+        B.fpq_quantize_nhwc(dev(x), f, sx, None, codes)
+    torch.cuda.synchronize()
+    got = codes.cpu().numpy()
+    assert np.all(got[Bn * H * W * Cp:] == 0xEE)
+    got = got[:Bn * H * W * Cp].reshape(Bn, H, W, Cp)
+    assert np.array_equal(got[..., :Cc], oracle.quantize(x, f, sx).transpose(0, 2, 3, 1))
+    assert np.all(got[..., Cc:] == 0)
