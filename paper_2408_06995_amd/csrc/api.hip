@@ -467,11 +467,57 @@ static int run_layer(const CodesOut* out, const void* x, int x_is_fp32, fpq_form
         return FPQ_ERR_WORKSPACE;
     if (!x_is_fp32 && (!workspace || workspace_bytes < part_bytes)) plan.splits = 1;
     float* partial = plan.splits > 1 ? reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + codes_bytes) : nullptr;
+    GemmArgs a;
+    memset(&a, 0, sizeof a);
+    a.wrows = static_cast<const uint8_t*>(packed_w) + kPackedRowsOffset;
+    a.sw = sw;
+    a.bias = bias;
+    a.sx = sx;
+    a.alpha = alpha;
+    a.y = y;
+    a.M = (int)M;
+    a.N = (int)Cout;
+    a.Kpad = (int)padded_k(Cin, (int64_t)kh * kw);
+    a.Kreal = (int)(Cp * kh * kw);
+    a.B = (int)B; a.H = (int)H; a.W = (int)W; a.Cp = (int)Cp;
+    a.Ho = (int)Ho; a.Wo = (int)Wo;
+    a.kh = kh; a.kw = kw; a.stride = stride; a.pad = pad;
+    a.conv_out = conv_out;
+    a.xkind = xkind; a.wkind = wkind;
+    a.xe = fx.ebits; a.xm = fx.mbits; a.xb = fx.bias;
+    a.we = fw.ebits; a.wm = fw.mbits; a.wb = fw.bias;
+    a.acc_mode = acc_mode;
+    a.accumulate = accumulate;
+    if (out) {
+        a.yq = out->yq;
+        a.act = act;
+        a.ldq = (int)(act == FPQ_ACT_GEGLU ? Cout / 2 : padded_channels(Cout));
+        a.ym = qy.m; a.yb = qy.b; a.yem = qy.em; a.yc = qy.c;
+        a.ykind = (out->f.ebits == 4 && out->f.mbits == 3 && out->f.bias == 7 && qy.c <= 448.0f) ? 1
+                  : (out->f.ebits == 5 && out->f.mbits == 2 && out->f.bias == 15 && qy.c <= 57344.0f) ? 2 : 0;
+        a.sy = out->s;
+        a.sy_dev = out->s_dev;
+    }
+    a.partial = partial;
+    a.splits = plan.splits;
+    a.tile = plan.tile;
+    a.x_bytes = (uint32_t)(B * H * W * Cp);
+    {
+        const int64_t wrow = is_four_bit(fw) ? a.Kpad / 2 : a.Kpad;
+        if (wrow * Cout >= (int64_t)1 << 31) return FPQ_ERR_SHAPE;
+        a.w_bytes = (uint32_t)(wrow * Cout);
+    }
     if (x_is_fp32) {
         if (reinterpret_cast<uintptr_t>(x) & 3) return FPQ_ERR_ALIGN;
         uint8_t* buf = static_cast<uint8_t*>(workspace);
         ScaleSrc ss{sx, sx_dev, nullptr, 0, 0.0f, nullptr};
         bool quantized = false;
+        if (dyn && !conv_out && Cp == Cin && M <= 16) {
+            // at most 16 rows: maximum, scale, codes and the layer itself in one launch
+            st = launch_gemm_skinny_dynamic(a, static_cast<const float*>(x), qx, qx.c, buf,
+                                            reinterpret_cast<float*>(buf + codes_bytes + part_bytes) + 1024, s);
+            if (st != FPQ_ERR_UNSUPPORTED) return st;
+        }
         if (dyn && !conv_out && Cp == Cin) {
             // a tensor of a few thousand elements: maximum, scale and codes by one workgroup in one launch
             float* dynbuf = reinterpret_cast<float*>(buf + codes_bytes + part_bytes);
@@ -513,48 +559,8 @@ static int run_layer(const CodesOut* out, const void* x, int x_is_fp32, fpq_form
         if (reinterpret_cast<uintptr_t>(x) & 15) return FPQ_ERR_ALIGN;
         xcodes = static_cast<const uint8_t*>(x);
     }
-    GemmArgs a;
-    memset(&a, 0, sizeof a);
     a.x = xcodes;
-    a.wrows = static_cast<const uint8_t*>(packed_w) + kPackedRowsOffset;
-    a.sw = sw;
-    a.bias = bias;
     a.sx_dev = sx_dev;
-    a.sx = sx;
-    a.alpha = alpha;
-    a.y = y;
-    a.M = (int)M;
-    a.N = (int)Cout;
-    a.Kpad = (int)padded_k(Cin, (int64_t)kh * kw);
-    a.Kreal = (int)(Cp * kh * kw);
-    a.B = (int)B; a.H = (int)H; a.W = (int)W; a.Cp = (int)Cp;
-    a.Ho = (int)Ho; a.Wo = (int)Wo;
-    a.kh = kh; a.kw = kw; a.stride = stride; a.pad = pad;
-    a.conv_out = conv_out;
-    a.xkind = xkind; a.wkind = wkind;
-    a.xe = fx.ebits; a.xm = fx.mbits; a.xb = fx.bias;
-    a.we = fw.ebits; a.wm = fw.mbits; a.wb = fw.bias;
-    a.acc_mode = acc_mode;
-    a.accumulate = accumulate;
-    if (out) {
-        a.yq = out->yq;
-        a.act = act;
-        a.ldq = (int)(act == FPQ_ACT_GEGLU ? Cout / 2 : padded_channels(Cout));
-        a.ym = qy.m; a.yb = qy.b; a.yem = qy.em; a.yc = qy.c;
-        a.ykind = (out->f.ebits == 4 && out->f.mbits == 3 && out->f.bias == 7 && qy.c <= 448.0f) ? 1
-                  : (out->f.ebits == 5 && out->f.mbits == 2 && out->f.bias == 15 && qy.c <= 57344.0f) ? 2 : 0;
-        a.sy = out->s;
-        a.sy_dev = out->s_dev;
-    }
-    a.partial = partial;
-    a.splits = plan.splits;
-    a.tile = plan.tile;
-    a.x_bytes = (uint32_t)(B * H * W * Cp);
-    {
-        const int64_t wrow = is_four_bit(fw) ? a.Kpad / 2 : a.Kpad;
-        if (wrow * Cout >= (int64_t)1 << 31) return FPQ_ERR_SHAPE;
-        a.w_bytes = (uint32_t)(wrow * Cout);
-    }
     if (!gemm_dma_applicable(a)) {   // operand pairing only the generic kernels serve
         a.tile = TILE_GENERIC;
         a.splits = 1;

@@ -227,6 +227,10 @@ int launch_pack_weights(const float* w, int64_t N, int64_t Cin, int taps, const 
                         const float* scale_in, const uint8_t* mask, uint8_t* packed_rows, float* scale_out,
                         uint8_t* codes_out, hipStream_t st);
 int launch_gemm(const GemmArgs& a, hipStream_t st);
+// One launch for a dynamically scaled linear layer with at most 16 rows (x: the fp32 activations; a.x is not used;
+// codes [M, K] and publish [scale, absmax] receive what the two-launch form leaves in the workspace).
+int launch_gemm_skinny_dynamic(const GemmArgs& a, const float* x, const QParams& qx, float maxval, uint8_t* codes,
+                               float* publish, hipStream_t st);
 bool gemm_dma_applicable(const GemmArgs& a);
 int launch_gemm_dma(const GemmArgs& a, hipStream_t st);
 int launch_gemm_dma_q(const GemmArgs& a, hipStream_t st);   // the same with the result as codes (a.yq)

@@ -489,10 +489,134 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const GemmArgs a)
     }
 }
 
+// The same layer straight from the fp32 activations with a dynamic per-tensor scale (x of at most 16 Ki elements,
+// rows of K % 16 == 0 values): every workgroup finds max |x| itself (the tensor is a few tens of KB, read from L2),
+// quantizes it into LDS and runs the MFMA steps of gemm_skinny_kernel on those codes: one launch instead of the
+// quantizer's and the layer's.  The weight loads of the first round go out before the activations are touched.
+// Codes, scale, K split and summation order are those of the two-launch form, so the result is bit-identical.
+template <int WKIND>
+__global__ __launch_bounds__(256) void gemm_skinny_dynamic_kernel(const GemmArgs a, const float4* __restrict__ x4, int n4,
+                                                                  QParams qx, float maxval, uint32_t* __restrict__ codes_out,
+                                                                  float* __restrict__ publish)
+{
+    constexpr bool W4 = kind_is_4bit(WKIND);
+    constexpr int U = 5;
+    __shared__ float red[3][64][4];
+    __shared__ float part[4];
+    __shared__ __attribute__((aligned(16))) uint8_t xcodes[16384];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r16 = lane & 15, kq = lane >> 4;
+    const int n0 = blockIdx.x * 16;
+    const int K = a.Kreal;
+    const int nsteps = (K + 63) / 64;
+    const bool has_m = r16 < a.M, has_n = n0 + r16 < a.N;
+    const uint8_t* wrow = a.wrows + (size_t)(has_n ? n0 + r16 : 0) * (W4 ? a.Kpad / 2 : a.Kpad);
+    const GenFmt nofmt{0, 0, 0};
+    auto load_w = [&](int s) -> uint4 {
+        const int k = 64 * s + 16 * kq;
+        const bool in = s < nsteps && k < K && has_n;
+        if (W4) {
+            const uint2 t = in ? *reinterpret_cast<const uint2*>(wrow + k / 2) : make_uint2(0u, 0u);
+            return make_uint4(t.x, 0u, t.y, 0u);
+        }
+        return in ? *reinterpret_cast<const uint4*>(wrow + k) : make_uint4(0u, 0u, 0u, 0u);
+    };
+    uint4 wv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) wv[u] = load_w(wave + 4 * u);
+    // ---- max |x|, scale, codes into LDS (element order of x: row-major [M, K])
+    float4 v[16];
+    float m = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const int i = e * 256 + threadIdx.x;
+        v[e] = i < n4 ? x4[i] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        m = fmaxf(m, fmaxf(fmaxf(fabsf(v[e].x), fabsf(v[e].y)), fmaxf(fabsf(v[e].z), fabsf(v[e].w))));
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    if (lane == 0) part[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
+    const float sx = (m == 0.0f) ? 1.0f : __fdiv_rn(m, maxval);
+    const float rx = __fdiv_rn(1.0f, sx);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const int i = e * 256 + threadIdx.x;
+        if (i < n4) {
+            const uint32_t c0 = quantize_nearest(v[e].x, rx, qx), c1 = quantize_nearest(v[e].y, rx, qx);
+            const uint32_t c2 = quantize_nearest(v[e].z, rx, qx), c3 = quantize_nearest(v[e].w, rx, qx);
+            const uint32_t word = c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+            reinterpret_cast<uint32_t*>(xcodes)[i] = word;
+            if (blockIdx.x == 0) codes_out[i] = word;      // the first workgroup leaves codes and scale where the
+        }                                                  // two-launch form does, for inspection
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        publish[0] = sx;
+        publish[1] = m;
+    }
+    __syncthreads();
+    // ---- the MFMA steps of gemm_skinny_kernel, activations from LDS
+    const uint8_t* xrow = xcodes + (size_t)(has_m ? r16 : 0) * K;
+    v4f_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int s0 = wave; s0 < nsteps; s0 += 4 * U) {
+        if (s0 != wave) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) wv[u] = load_w(s0 + 4 * u);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int k = 64 * (s0 + 4 * u) + 16 * kq;
+            const bool in = s0 + 4 * u < nsteps && k < K && has_m;
+            const uint4 xv = in ? *reinterpret_cast<const uint4*>(xrow + k) : make_uint4(0u, 0u, 0u, 0u);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(decode8<OPK_FP8>(xv.x, xv.y, nofmt),
+                                                          decode8<WKIND>(wv[u].x, wv[u].y, nofmt), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(decode8<OPK_FP8>(xv.z, xv.w, nofmt),
+                                                          decode8<WKIND>(wv[u].z, wv[u].w, nofmt), acc, 0, 0, 0);
+        }
+    }
+    if (wave > 0) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[wave - 1][lane][r] = acc[r];
+    }
+    __syncthreads();
+    if (wave == 0) {
+        const int n = n0 + r16;
+        if (n < a.N) {
+            const float sc = sx * a.alpha * a.sw[n];
+            const float bv = a.bias ? a.bias[n] : 0.0f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int mrow = 4 * kq + r;
+                if (mrow < a.M)
+                    a.y[(size_t)mrow * a.N + n] = (acc[r] + red[0][lane][r] + red[1][lane][r] + red[2][lane][r]) * sc + bv;
+            }
+        }
+    }
+}
+
 static bool skinny_applicable(const GemmArgs& a)
 {
     return !a.conv_out && a.M <= 16 && a.acc_mode == FPQ_ACC_FP32 && a.xkind == OPK_FP8 &&
            (a.wkind == OPK_FP8 || a.wkind == OPK_FP4) && !a.yq && !a.accumulate && a.splits == 1;
+}
+
+// FPQ_OK when the one-launch form of a dynamically scaled linear layer with at most 16 rows ran,
+// FPQ_ERR_UNSUPPORTED when it does not apply (shape, formats, alignment): the caller then quantizes and calls launch_gemm.
+int launch_gemm_skinny_dynamic(const GemmArgs& a, const float* x, const QParams& qx, float maxval, uint8_t* codes,
+                               float* publish, hipStream_t st)
+{
+    const size_t n = (size_t)a.M * a.Kreal;
+    if (!skinny_applicable(a) || a.M < 1 || a.N < 1 || n > 16384 || (a.Kreal & 15) || (reinterpret_cast<uintptr_t>(x) & 15))
+        return FPQ_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)((a.N + 15) / 16));
+    if (a.wkind == OPK_FP8)
+        hipLaunchKernelGGL(gemm_skinny_dynamic_kernel<OPK_FP8>, grid, dim3(256), 0, st, a, reinterpret_cast<const float4*>(x),
+                           (int)(n >> 2), qx, maxval, reinterpret_cast<uint32_t*>(codes), publish);
+    else
+        hipLaunchKernelGGL(gemm_skinny_dynamic_kernel<OPK_FP4>, grid, dim3(256), 0, st, a, reinterpret_cast<const float4*>(x),
+                           (int)(n >> 2), qx, maxval, reinterpret_cast<uint32_t*>(codes), publish);
+    return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
 }
 
 int launch_gemm(const GemmArgs& a, hipStream_t st)

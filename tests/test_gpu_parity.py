@@ -404,12 +404,12 @@ def test_conv_one_hot_taps_exact():
         assert np.array_equal(y.cpu().numpy(), want)
 
 
-@pytest.mark.parametrize("kind,small", [("linear", False), ("linear", True), ("conv", False)])
+@pytest.mark.parametrize("kind,small", [("linear", False), ("linear", True), ("linear", None), ("conv", False)])
 def test_dynamic_scale_of_an_all_zero_input(kind, small):
     """absmax = 0: the scale is 1 (not 0 / c), every code is +0 and the result is the bias."""
     fx, fw = synth.E4M3, synth.E2M1
     if kind == "linear":
-        M, K, N = (300, 320, 160) if small is False else (8, 320, 160)
+        M, K, N = {False: (300, 320, 160), True: (8, 320, 160), None: (40, 320, 160)}[small]
         w = synth.weights((N, K), 91)
         x = torch.zeros((M, K), device=DEV)
     else:
