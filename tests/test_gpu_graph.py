@@ -11,11 +11,13 @@ from gpu_util import DEV, dev, gpu_pack
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("case", ["conv_dynamic_splitk", "linear_dynamic", "linear_codes_out_geglu"])
+@pytest.mark.parametrize("case", ["conv_dynamic_splitk", "linear_dynamic", "linear_dynamic_8_rows", "linear_codes_out_geglu"])
 def test_graph_replays_equal_eager(case):
     fx, fw = synth.E4M3, synth.E2M1
     if case == "conv_dynamic_splitk":
         shape, wshape = (1, 640, 16, 16), (160, 640, 3, 3)            # deep K, few tiles: K slices + reduction kernel
+    elif case == "linear_dynamic_8_rows":
+        shape, wshape = (8, 1280), (1280, 1280)                       # the one-launch form of the layers with <= 16 rows
     else:
         shape, wshape = (4096, 320), (640, 320)
     w = synth.weights(wshape, 31)
@@ -30,7 +32,7 @@ def test_graph_replays_equal_eager(case):
         def call():
             B.fpq_conv2d(x, B.FPQ_X_FP32_DYNAMIC, fx, 0.0, None, packed, fw, sw_t, None, y, Bn, Cin, H, W, Cout, 3, 3, 1, 1,
                          B.FPQ_ACC_FP32, ws)
-    elif case == "linear_dynamic":
+    elif case in ("linear_dynamic", "linear_dynamic_8_rows"):
         M, K = shape
         N = wshape[0]
         y = torch.empty((M, N), device=DEV)
