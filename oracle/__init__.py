@@ -234,6 +234,26 @@ def geglu(V):
     return (blocks[:, :, 0, :] * gelu(blocks[:, :, 1, :])).reshape(M, N // 2)
 
 
+def geglu_plain(V):
+    """Gated GELU as a feed-forward block defines it: the projection's result holds all values in the first half of
+    its columns and all gates in the second half: [M, N] -> [M, N / 2], out[:, i] = V[:, i] * gelu(V[:, N / 2 + i])."""
+    V = np.asarray(V, dtype=np.float64)
+    half = V.shape[1] // 2
+    return V[:, :half] * gelu(V[:, half:])
+
+
+def geglu_interleaved_rows(N):
+    """The one-time reordering of a projection's N output channels (weight rows, scales, biases) from the plain
+    layout of geglu_plain to the blocked layout of geglu: entry r of the result is the plain index that moves to
+    position r.  Position 32 B + i (i < 16) takes value channel 16 B + i, position 32 B + 16 + i its gate N / 2 + 16 B + i."""
+    half = N // 2
+    order = np.empty(N, dtype=np.int64)
+    for r in range(N):
+        blk, i = divmod(r, 32)
+        order[r] = 16 * blk + i if i < 16 else half + 16 * blk + (i - 16)
+    return order
+
+
 def requantize(Y, fmt, scale):
     """A layer's result as the next quantized layer's input codes (Section V: every convolution / linear input is
     quantized): the fp32 value of each output through the activation quantizer of Eq. (6)-(9)."""

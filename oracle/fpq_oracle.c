@@ -34,8 +34,8 @@
  *   - Algorithm 1 (Section V-A) starts from prev_mse = 0 and keeps a candidate only when
  *     prev_mse > curr_mse, which as printed never accepts anything: read as prev_mse =
  *     +infinity (first strict minimum in scan order, encodings outer, biases inner);
- *   - its bias candidates are "evenly spaced values between the minimum and maximum of the
- *     data", turned into biases by Eq. (7): read on magnitudes (the grid is symmetric) as
+ *   - its bias candidates come from equally spaced points of the data's range, each turned
+ *     into a bias by Eq. (7): read on magnitudes (the grid is symmetric) as
  *     the max values c_j = absmax * (j + 1) / J, j = 0 .. J-1; the real-valued bias of c_j
  *     is carried as the integer bias b0 = 2^(e-1) plus the scale c_j / c0, c0 = Eq. (7) at
  *     b0 (the grid of a real bias is a scaled copy of the grid of an integer one);
