@@ -714,7 +714,7 @@ def test_geglu_plain_layout_and_the_row_reordering_to_the_blocked_one():
     V = rng.normal(0, 2, (7, 128))
     out = oracle.geglu_plain(V)
     a, g = torch.from_numpy(V).chunk(2, dim=1)
-    assert np.allclose(out, (a * torch.nn.functional.gelu(g)).numpy(), rtol=1e-12, atol=1e-300)
+    assert np.allclose(out, (a * torch.nn.functional.gelu(g)).numpy(), rtol=1e-12, atol=1e-13)   # torch forms 1 + erf: absolute accuracy only
     for m in range(7):
         for o in range(64):
             want = V[m, o] * 0.5 * V[m, 64 + o] * (1 + math.erf(V[m, 64 + o] / math.sqrt(2)))
