@@ -9,7 +9,8 @@
  *
  * Conventions
  *   - A format is (ebits e, mbits m, integer bias b, max value c); 1 + e + m <= 8, e >= 1, m >= 0,
- *     |b| <= 64.  maxval == 0 selects the paper's closed form, Eq. (7).  A non-zero maxval must be a
+ *     |b| <= 64 and 2^e - b - 1 <= 104 + m (the largest value stays below 2^(106 + m); of the
+ *     encodings above only E7M0 below bias 23 and E6M1 below bias -42 are excluded).  maxval == 0 selects the paper's closed form, Eq. (7).  A non-zero maxval must be a
  *     value of the (e, m, b) grid and must not exceed Eq. (7) (hardware E4M3 is (4, 3, 7, 448)).
  *   - A code is sign << (e+m) | p << m | f, one per byte for every format in device buffers that
  *     feed fpq_gemm / fpq_conv2d.  fpq_quantize writes two codes per byte when 1 + e + m <= 4
@@ -53,7 +54,7 @@ typedef enum fpq_status {
     FPQ_ERR_WORKSPACE = -6,   /* workspace missing or too small */
     FPQ_ERR_LAUNCH = -7,      /* the HIP runtime reported an error at launch */
     FPQ_ERR_UNSUPPORTED = -8, /* valid arguments the library has no kernel for */
-    FPQ_ERR_PACKED = -9       /* packed weight buffer does not match the arguments */
+    FPQ_ERR_PACKED = -9       /* fpq_packed_check: the packed weight buffer does not match the arguments */
 } fpq_status;
 
 /* Accumulation arithmetic of fpq_gemm / fpq_conv2d.
@@ -161,8 +162,8 @@ int fpq_search_format(const float *x, size_t n, const int32_t *ebits, const int3
  * matrix instruction.  workspace: fpq_rl_workspace_size bytes, 256-byte aligned, no initialisation.
  * Size limits (FPQ_ERR_SHAPE beyond them): N K < 2^31, M N < 2^31, M < 2^23; lr and reg_weight finite and
  * >= 0 (FPQ_ERR_SCALE otherwise). */
-/* A convolution takes part as the linear layer on its patch matrix (the paper: "can be applied to other
- * layers such as Convolutional"): fpq_rl_im2col writes, for x NCHW [B, C, H, W] fp32, the matrix
+/* A convolution takes part as the linear layer on its patch matrix (Section V-B presents the method on a linear
+ * layer and notes that it carries over to other layer types, convolutions among them): fpq_rl_im2col writes, for x NCHW [B, C, H, W] fp32, the matrix
  * a[B * Ho * Wo, C * kh * kw] whose row (b, ho, wo) is the receptive field of that output pixel in the
  * order of the flattened weight [Cout, (ci, kh, kw)], zero where it reaches into the padding; w[N, K] is
  * then the weight tensor as it stands, K = C * kh * kw, and the learned mask has the weight's shape. */
@@ -230,9 +231,10 @@ int fpq_pack_weights(const float *w, int64_t N, int64_t Cin, int kh, int kw, fpq
 
 /* Reads the header of a packed weight buffer back (synchronises `stream`; the only entry point that
  * waits for the device) and compares it with the arguments a layer call is about to pass: FPQ_OK, or
- * FPQ_ERR_FORMAT (not a packed buffer, or another format / max value) or FPQ_ERR_SHAPE (other N, Cin,
- * kh, kw).  The layer calls themselves are asynchronous and do not check the header: passing them a
- * buffer packed for another shape or format is the caller's error. */
+ * FPQ_ERR_PACKED (not a packed buffer, another format or max value, or other N, Cin, kh, kw).  The
+ * layer calls themselves are asynchronous and do not check the header (reading it back would make every
+ * layer call wait for the device): passing them a buffer packed for another shape or format is the
+ * caller's error, which this call lets the caller rule out once per buffer. */
 int fpq_packed_check(const void *packed, int64_t N, int64_t Cin, int kh, int kw, fpq_format_t f,
                      void *stream);
 
@@ -270,6 +272,25 @@ int fpq_conv2d(const void *x, int x_is_fp32, fpq_format_t fx, float sx, const fl
                const void *packed_w, fpq_format_t fw, const float *sw, const float *bias, float *y,
                int64_t B, int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh, int kw, int stride,
                int pad, int acc_mode, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Read-only query (host, no GPU): which kernel fpq_gemm / fpq_conv2d launch for a shape and into how many K slices
+ * they cut it, given a workspace of the size the *_workspace_size functions state and operands in the hardware's
+ * E4M3 / E2M1 encodings (other operand pairings may take FPQ_KERNEL_SMALL_TILE, unsliced, whatever the shape).
+ * With more than one slice the layer kernel writes partial sums to the workspace and a reduction kernel adds them.
+ * For tests and benchmarks that have to state, or to cover, every launch configuration a workload uses. */
+typedef enum fpq_kernel {
+    FPQ_KERNEL_SMALL_TILE = 0, /* register-staged 128 x 128 / 64 x 64 tiles: any shape */
+    FPQ_KERNEL_256x160 = 1,    /* persistent 256 x 160 tiles, three LDS stages */
+    FPQ_KERNEL_128x160 = 2,    /* persistent 128 x 160 tiles, two LDS stages, two workgroups per compute unit */
+    FPQ_KERNEL_ROWS16 = 3      /* linear layers with at most 16 rows: K split over the wavefronts of a workgroup */
+} fpq_kernel;
+typedef struct fpq_plan {
+    int32_t kernel;   /* fpq_kernel */
+    int32_t k_slices; /* >= 1 */
+} fpq_plan_t;
+int fpq_gemm_plan(int64_t M, int64_t N, int64_t K, fpq_plan_t *plan);
+int fpq_conv2d_plan(int64_t B, int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh, int kw, int stride,
+                    int pad, fpq_plan_t *plan);
 
 /* ---- the same layers with the result handed to the next quantized layer as codes -------------
  *

@@ -26,6 +26,13 @@ class fpq_format_t(C.Structure):
     _fields_ = [("ebits", C.c_int32), ("mbits", C.c_int32), ("bias", C.c_int32), ("maxval", C.c_float)]
 
 
+class fpq_plan_t(C.Structure):
+    _fields_ = [("kernel", C.c_int32), ("k_slices", C.c_int32)]
+
+
+FPQ_KERNEL_SMALL_TILE, FPQ_KERNEL_256x160, FPQ_KERNEL_128x160, FPQ_KERNEL_ROWS16 = 0, 1, 2, 3
+
+
 class FpqError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
@@ -105,6 +112,10 @@ def lib():
     L.fpq_count_zeros_workspace_size.argtypes = [sz]
     L.fpq_count_zeros.restype = i32
     L.fpq_count_zeros.argtypes = [vp, i32, sz, F, vp, vp, sz, vp]
+    L.fpq_gemm_plan.restype = i32
+    L.fpq_gemm_plan.argtypes = [i64, i64, i64, C.POINTER(fpq_plan_t)]
+    L.fpq_conv2d_plan.restype = i32
+    L.fpq_conv2d_plan.argtypes = [i64] * 5 + [i32] * 4 + [C.POINTER(fpq_plan_t)]
     _lib = L
     return L
 
@@ -114,7 +125,8 @@ EXPORTS = ["fpq_strerror", "fpq_format_max", "fpq_format_check", "fpq_bias_to_sc
            "fpq_dequantize", "fpq_packed_size", "fpq_pack_weights", "fpq_gemm_workspace_size", "fpq_gemm",
            "fpq_conv2d_workspace_size", "fpq_conv2d", "fpq_search_workspace_size", "fpq_search_format",
            "fpq_count_zeros_workspace_size", "fpq_count_zeros", "fpq_gemm_codes_out", "fpq_conv2d_codes_out",
-           "fpq_rl_workspace_size", "fpq_rl_init_alpha", "fpq_rl_step", "fpq_rl_mask", "fpq_packed_check", "fpq_rl_im2col"]
+           "fpq_rl_workspace_size", "fpq_rl_init_alpha", "fpq_rl_step", "fpq_rl_mask", "fpq_packed_check", "fpq_rl_im2col",
+           "fpq_gemm_plan", "fpq_conv2d_plan"]
 
 
 def fmt(f):
@@ -177,6 +189,20 @@ def fpq_gemm_workspace_size(M, N, K, x_is_fp32):
 
 def fpq_conv2d_workspace_size(B, Cin, H, W, Cout, kh, kw, stride, pad, x_is_fp32):
     return lib().fpq_conv2d_workspace_size(B, Cin, H, W, Cout, kh, kw, stride, pad, int(x_is_fp32))
+
+
+def fpq_gemm_plan(M, N, K):
+    """(kernel, k_slices) of a linear layer."""
+    p = fpq_plan_t()
+    _check(lib().fpq_gemm_plan(M, N, K, C.byref(p)), "fpq_gemm_plan")
+    return p.kernel, p.k_slices
+
+
+def fpq_conv2d_plan(B, Cin, H, W, Cout, kh, kw, stride, pad):
+    """(kernel, k_slices) of a convolution."""
+    p = fpq_plan_t()
+    _check(lib().fpq_conv2d_plan(B, Cin, H, W, Cout, kh, kw, stride, pad, C.byref(p)), "fpq_conv2d_plan")
+    return p.kernel, p.k_slices
 
 
 # ---- device entry points (torch tensors in, status checked)

@@ -10,7 +10,13 @@ using namespace fpq;
 
 namespace {
 
-bool em_ok(int e, int m, int b) { return e >= 1 && m >= 0 && 1 + e + m <= 8 && b >= -64 && b <= 64; }
+// |b| <= 64 keeps every grid value and the decoders' constants normal fp32 numbers; the last condition keeps the
+// rounding constant of the encoder (2^23 times the step of the top binade, exponent field 2^e - 1 - b - m + 150)
+// a finite fp32 number: it excludes only encodings whose largest value exceeds 2^(105 + m), e.g. E7M0 below bias 23.
+bool em_ok(int e, int m, int b)
+{
+    return e >= 1 && m >= 0 && 1 + e + m <= 8 && b >= -64 && b <= 64 && (1 << e) - b - 1 <= 104 + m;
+}
 
 double eq7_max(int e, int m, int b) { return (2.0 - ldexp(1.0, -m)) * ldexp(1.0, (1 << e) - b - 1); }
 
@@ -338,9 +344,9 @@ int fpq_packed_check(const void* packed, int64_t N, int64_t Cin, int kh, int kw,
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (hipMemcpyAsync(&h, packed, sizeof h, hipMemcpyDeviceToHost, s) != hipSuccess) return FPQ_ERR_LAUNCH;
     if (hipStreamSynchronize(s) != hipSuccess) return FPQ_ERR_LAUNCH;
-    if (h.magic != kPackedMagic || h.layout != 1) return FPQ_ERR_FORMAT;
-    if (h.ebits != f.ebits || h.mbits != f.mbits || h.bias != f.bias || h.maxval != q.c) return FPQ_ERR_FORMAT;
-    if (h.N != N || h.Cin != Cin || h.kh != kh || h.kw != kw) return FPQ_ERR_SHAPE;
+    if (h.magic != kPackedMagic || h.layout != 1) return FPQ_ERR_PACKED;
+    if (h.ebits != f.ebits || h.mbits != f.mbits || h.bias != f.bias || h.maxval != q.c) return FPQ_ERR_PACKED;
+    if (h.N != N || h.Cin != Cin || h.kh != kh || h.kw != kw) return FPQ_ERR_PACKED;
     return FPQ_OK;
 }
 
@@ -401,6 +407,35 @@ size_t fpq_conv2d_workspace_size(int64_t B, int64_t Cin, int64_t H, int64_t W, i
            align_up(split_workspace_bytes(plan_gemm(B * Ho * Wo, Cout, padded_k(Cin, (int64_t)kh * kw)), B * Ho * Wo, Cout),
                     256) +
            (x_is_fp32 == FPQ_X_FP32_DYNAMIC ? kDynScaleBytes : 0);
+}
+
+static void fill_plan(const GemmPlan& p, int64_t M, bool linear, fpq_plan_t* out)
+{
+    out->kernel = p.tile == TILE_256x160_S3 ? FPQ_KERNEL_256x160
+                  : p.tile == TILE_128x160_S2 ? FPQ_KERNEL_128x160
+                  : (linear && M <= 16)       ? FPQ_KERNEL_ROWS16
+                                              : FPQ_KERNEL_SMALL_TILE;
+    out->k_slices = p.splits;
+}
+
+int fpq_gemm_plan(int64_t M, int64_t N, int64_t K, fpq_plan_t* plan)
+{
+    if (!plan) return FPQ_ERR_NULL;
+    if (M <= 0 || K <= 0 || N <= 0) return FPQ_ERR_SHAPE;
+    fill_plan(plan_gemm(M, N, padded_k(K, 1)), M, true, plan);
+    return FPQ_OK;
+}
+
+int fpq_conv2d_plan(int64_t B, int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh, int kw, int stride, int pad,
+                    fpq_plan_t* plan)
+{
+    if (!plan) return FPQ_ERR_NULL;
+    if (B <= 0 || Cin <= 0 || H <= 0 || W <= 0 || Cout <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0)
+        return FPQ_ERR_SHAPE;
+    if (H + 2 * pad < kh || W + 2 * pad < kw) return FPQ_ERR_SHAPE;
+    const int64_t Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
+    fill_plan(plan_gemm(B * Ho * Wo, Cout, padded_k(Cin, (int64_t)kh * kw)), B * Ho * Wo, false, plan);
+    return FPQ_OK;
 }
 
 // Where a layer's result goes when it leaves as codes for the next quantized layer.

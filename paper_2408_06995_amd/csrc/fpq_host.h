@@ -4,7 +4,6 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
-#include <stdlib.h>
 
 #include <atomic>
 
@@ -132,16 +131,6 @@ static inline GemmPlan plan_gemm(int64_t M, int64_t N, int64_t Kpad)
 {
     GemmPlan p{TILE_GENERIC, 1};
     if (N % 160 != 0 || M < 1) return p;
-#ifdef FPQ_TUNING   // tuning builds only: FPQ_FORCE_TILE / FPQ_FORCE_SPLITS override the plan, for sweeps
-    if (const char* ft = getenv("FPQ_FORCE_TILE")) {
-        p.tile = atoi(ft);
-        const char* fs = getenv("FPQ_FORCE_SPLITS");
-        p.splits = fs ? atoi(fs) : 1;
-        const int64_t nkk = Kpad / 128;
-        if (p.splits > nkk) p.splits = (int)nkk;
-        return p;
-    }
-#endif
     if (M <= 16) return p;   // at most 16 rows: the register-staged kernels (linear layers: one that splits K over its waves)
     const int64_t nk = Kpad / 128;
     // Small outputs with a short K: the register-staged kernel with its 64 x 64 tiles spreads them over more

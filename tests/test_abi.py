@@ -131,3 +131,25 @@ def test_argument_validation_without_gpu():
     assert L.fpq_count_zeros(C.c_void_p(4098), 1, 100, f, p, p, 8192, None) == -5
     assert L.fpq_strerror(-2).decode().startswith("invalid ExMy")
     assert L.fpq_strerror(0) == b"ok"
+
+
+def test_plan_query_and_format_range():
+    L = B.lib()
+    assert B.fpq_gemm_plan(8, 1280, 1280) == (B.FPQ_KERNEL_ROWS16, 1)
+    assert B.fpq_gemm_plan(616, 320, 768) == (B.FPQ_KERNEL_SMALL_TILE, 1)
+    assert B.fpq_gemm_plan(4096, 333, 640) == (B.FPQ_KERNEL_SMALL_TILE, 1)          # N not a multiple of 160
+    k, s = B.fpq_gemm_plan(512, 1280, 5120)
+    assert k == B.FPQ_KERNEL_128x160 and s > 1
+    assert B.fpq_gemm_workspace_size(512, 1280, 5120, 0) == s * 512 * 1280 * 4
+    k, s = B.fpq_conv2d_plan(8, 1280, 32, 32, 1280, 3, 3, 1, 1)
+    assert k == B.FPQ_KERNEL_256x160 and s == 1
+    p = B.fpq_plan_t()
+    assert L.fpq_gemm_plan(0, 8, 8, C.byref(p)) == -4
+    assert L.fpq_gemm_plan(8, 8, 8, None) == -1
+    assert L.fpq_conv2d_plan(1, 16, 2, 2, 8, 3, 3, 1, 0, C.byref(p)) == -4
+    # encodings whose largest value would overflow the encoder's fp32 rounding constant are rejected
+    assert B.fpq_format_check((7, 0, 23, 0.0)) == 0 and B.fpq_format_check((7, 0, 22, 0.0)) == -2
+    assert B.fpq_format_check((6, 1, -42, 0.0)) == 0 and B.fpq_format_check((6, 1, -43, 0.0)) == -2
+    assert B.fpq_format_max(7, 0, 0) == 0.0
+    assert B.fpq_format_check((5, 2, -64, 0.0)) == 0 and B.fpq_format_check((4, 3, -64, 0.0)) == 0
+    assert L.fpq_strerror(-9).decode().startswith("packed weights")

@@ -180,6 +180,39 @@ def test_linear_activation_then_codes(M, K, N, fw, fy, acc, act):
         assert miss < 0.005
 
 
+def test_gated_projection_given_in_the_plain_values_then_gates_layout():
+    """A feed-forward projection as a model stores it, all value channels before all gate channels.  The caller
+    reorders the weight rows (and the bias) once into blocks of 16 values + 16 gates, as the header of the gated
+    form asks; the codes that come out are then, column for column, those of the block's own definition
+    values * gelu(gates) evaluated by the oracle on the result of the layer with the weights as stored."""
+    M, K, N = 300, 320, 640
+    fx, fw, fy = E4M3, E2M1, E4M3
+    x = synth.activations((M, K), 9001)
+    w = synth.weights((N, K), 9501) * 4.0
+    h = synth.rounding_mask((N, K), 9751)
+    bias = np.linspace(-1, 1, N).astype(np.float32)
+    sx, xq, wq, sw = oracle_linear_inputs(x, w, h, fx, fw)
+    Y, T = oracle.gemm(xq, fx, sx, wq, fw, sw, bias)                  # plain layout
+    O = oracle.geglu_plain(Y)
+    t = 1e-5 * T + 1e-6
+    half = N // 2
+    a, g, ta, tg = Y[:, :half], Y[:, half:], t[:, :half], t[:, half:]
+    G = oracle.gelu(g)
+    dG = 1.13 * tg + 4e-7 * np.abs(g) + 1e-6 * np.abs(G) + 1e-12
+    tol = np.abs(G) * ta + (np.abs(a) + ta) * dG + 1e-6 * np.abs(a * G)
+    sy = out_scale(O, fy)
+    order = oracle.geglu_interleaved_rows(N)                           # the caller's one-time reordering
+    packed, sw_t, _ = gpu_pack(w[order], fw, h[order], want_codes=False)
+    assert np.array_equal(sw_t.cpu().numpy(), sw[order])               # per-channel scales move with their rows
+    yq = torch.full((M, half), 0xEE, dtype=torch.uint8, device=DEV)
+    ws = torch.empty(max(256, B.fpq_gemm_workspace_size(M, N, K, 0)), dtype=torch.uint8, device=DEV)
+    B.fpq_gemm_codes_out(dev(xq), 0, fx, sx, None, packed, fw, sw_t, dev(bias[order]), fy, sy, None, yq, M, N, K,
+                         B.FPQ_ACC_FP32 | B.FPQ_ACT_GEGLU, ws)
+    torch.cuda.synchronize()
+    miss = check_codes_interval(yq.cpu().numpy(), O, tol, fy, sy, "plain-layout gated projection")
+    assert miss < 0.005
+
+
 def test_feed_forward_projection_at_full_size_sampled_rows():
     """The transformer-block projection of configuration 3 (16384 x 320 -> 2560) as the U-Net runs it: gated GELU, then
     codes for the output layer.  All of it runs on the GPU in the bench's launch configuration; the oracle computes

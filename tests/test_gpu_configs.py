@@ -132,25 +132,109 @@ def test_config4_conv_w4a8_and_non_native_sweep():
     check_layer(L, x, w, h, synth.E3M4, synth.E3M0, (B.FPQ_ACC_FP32,), n_random=200, seed=5)
 
 
-CFG5_PICKS = ["time.fc1", "conv_in", "down0.res0.conv1", "down0.attn0.attn2.k", "down0.downsample", "down1.res0.skip",
-              "down2.attn0.ff.geglu", "mid.res0.conv1", "up3.res0.conv1", "up2.res2.skip", "up0.res0.conv1",
-              "up0.attn2.ff.out", "conv_out"]
+# ---- configuration 5: one representative of every distinct layer shape of the 250-layer set
+
+def layer_class(L):
+    return (L.kind, L.k if L.kind == "conv" else 1, L.stride if L.kind == "conv" else 1, L.M, L.K, L.N)
 
 
-@pytest.mark.parametrize("name", CFG5_PICKS)
-def test_config5_sampled_layers(name):
-    """Layers of the full U-Net set at batch 8, inputs drawn on the device as bench.py draws them."""
-    layers = synth.unet_layers()
-    li = [l.name for l in layers].index(name)
-    L = layers[li]
+def layer_plan(L):
+    """(kernel, K slices) the library states for this layer's shape."""
+    if L.kind == "conv":
+        return B.fpq_conv2d_plan(L.B, L.Cin, L.H, L.W, L.Cout, L.k, L.k, L.stride, L.pad)
+    return B.fpq_gemm_plan(L.M, L.N, L.K)
+
+
+def cfg5_classes():
+    """[(index of the first layer of the class in the layer list, layer)] in order of first appearance."""
+    seen, out = set(), []
+    for li, L in enumerate(synth.unet_layers()):
+        c = layer_class(L)
+        if c not in seen:
+            seen.add(c)
+            out.append((li, L))
+    return out
+
+
+CFG5_CLASSES = cfg5_classes()
+PLANS_RUN = set()   # (layer kind, kernel, K slices) of the class tests that have run in this process
+
+
+def sample_positions_large(M, seed):
+    """Rows for a layer too large to compare on every tile: first and last row of the first, the last and 24 random
+    128-row tiles (which are also the corners of the 256-row tiles they fall in), plus 32 random rows."""
+    if M <= 4096:
+        return sample_positions(M, 32, seed)
+    rng = np.random.default_rng(seed)
+    nt = (M + 127) // 128
+    tiles = np.unique(np.concatenate([[0, nt - 1], rng.integers(0, nt, 24)]))
+    rows = np.concatenate([tiles * 128, np.minimum(tiles * 128 + 127, M - 1), rng.integers(0, M, 32), [0, M - 1]])
+    return np.unique(rows)
+
+
+def check_layer_rows(L, x, w, h, fx, fw, acc, pos, what):
+    """As check_layer, on the given output rows / pixels, one accumulate mode, without re-checking the operand codes."""
+    x_t, w_t = dev(x), dev(w)
+    h_t = None if h is None else dev(h)
+    sx = oracle.scale_from_absmax(oracle.absmax(x), fx[3])
+    xq = oracle.quantize(x, fx, sx)
+    wq, sw = oracle.pack_weights(w, fw, h)
+    bias = np.linspace(-0.3, 0.3, L.N).astype(np.float32)
+    if L.kind == "conv":
+        Y, T = oracle.conv2d(xq, fx, sx, wq.reshape(L.Cout, L.Cin, L.k, L.k), fw, sw, bias, stride=L.stride, pad=L.pad,
+                             pix=pos)
+    else:
+        Y, T = oracle.gemm(xq, fx, sx, wq.reshape(L.N, L.K), fw, sw, bias, rows=pos)
+    y, sc, ws, wcodes, sw_t = run_layer_gpu(L, x_t, w_t, h_t, fx, fw, acc, dev(bias))
+    assert sc[0] == np.float32(oracle.absmax(x)) and sc[1] == np.float32(sx), what
+    assert np.array_equal(wcodes.cpu().numpy(), wq.reshape(-1)), "weight codes " + what
+    assert np.array_equal(sw_t.cpu().numpy(), sw), what
+    yh = y.cpu().numpy()
+    assert not np.isnan(yh).any(), "unwritten outputs " + what
+    if L.kind == "conv":
+        yv = yh.reshape(L.B, L.Cout, -1)
+        hw = yv.shape[2]
+        got_y = yv[pos // hw, :, pos % hw]
+    else:
+        got_y = yh.reshape(L.M, L.N)[pos]
+    return check_close(got_y, Y, T, rel=1e-5, what=what)
+
+
+@pytest.mark.parametrize("li,L", CFG5_CLASSES, ids=["%03d_%s" % (li, L.name) for li, L in CFG5_CLASSES])
+def test_config5_every_shape_class(li, L):
+    """Every distinct (kind, kernel size, stride, M, K, N) of the U-Net layer set at batch 8, with the inputs drawn on
+    the device as bench.py draws them, through the bench's dynamic-scale call in the fp32-accumulate mode: W8A8
+    (round-to-nearest E4M3 weights) and W4A8 (E2M1 weights with a rounding mask), on tile-corner and random rows the
+    oracle computes one by one.  The launch configuration is the one the benchmark times for this class."""
     sx_seed, sw_seed, sh_seed = synth.seeds(5, li)
     kk = L.k if L.kind == "conv" else 1
     x_t = synth.activations_torch((L.B, L.Cin, L.H, L.W) if L.kind == "conv" else (L.M, L.K), sx_seed, DEV)
     w_t = synth.weights_torch((L.Cout, L.Cin, kk, kk), sw_seed, DEV)
     h_t = synth.rounding_mask_torch((L.Cout, L.Cin, kk, kk), sh_seed, DEV)
     x, w, h = x_t.cpu().numpy(), w_t.cpu().numpy(), h_t.cpu().numpy()
-    big = synth.flops(L) > 2e10
-    check_layer(L, x, w, None, synth.E4M3, synth.E4M3, (B.FPQ_ACC_FP32,), n_random=24 if big else 64, seed=li,
-                full=(synth.flops(L) < 2e9))
-    check_layer(L, x, w, h, synth.E4M3, synth.E2M1, (B.FPQ_ACC_FP32, B.FPQ_ACC_FP8_MFMA), n_random=24 if big else 64,
-                seed=li + 1, full=(synth.flops(L) < 2e9))
+    del x_t, w_t, h_t
+    pos = sample_positions_large(L.M, li)
+    kernel, slices = layer_plan(L)
+    # the slice count is visible from outside: the workspace of the codes form holds exactly the partial sums
+    if L.kind == "conv":
+        part = B.fpq_conv2d_workspace_size(L.B, L.Cin, L.H, L.W, L.Cout, L.k, L.k, L.stride, L.pad, 0)
+    else:
+        part = B.fpq_gemm_workspace_size(L.M, L.N, L.K, 0)
+    want = slices * L.M * L.N * 4 if slices > 1 else 0
+    assert part == (want + 255) // 256 * 256
+    check_layer_rows(L, x, w, None, synth.E4M3, synth.E4M3, B.FPQ_ACC_FP32, pos, "%s W8A8" % L.name)
+    check_layer_rows(L, x, w, h, synth.E4M3, synth.E2M1, B.FPQ_ACC_FP32, pos, "%s W4A8" % L.name)
+    PLANS_RUN.add((L.kind, kernel, slices))
+
+
+def test_config5_classes_cover_every_plan_of_the_layer_set():
+    """The launch configurations (layer kind, kernel, K slices) of all 250 layers are exactly those of the class
+    representatives above; and, when those tests ran in this process, exactly those that were compared."""
+    layers = synth.unet_layers()
+    assert len(layers) == 250 and len(CFG5_CLASSES) == len({layer_class(L) for L in layers})
+    all_plans = {(L.kind,) + tuple(layer_plan(L)) for L in layers}
+    class_plans = {(L.kind,) + tuple(layer_plan(L)) for _, L in CFG5_CLASSES}
+    assert all_plans == class_plans
+    assert any(k == B.FPQ_KERNEL_256x160 and s > 1 for _, k, s in all_plans), "the sliced 256-row plan is part of the set"
+    if len(PLANS_RUN) >= len(class_plans):
+        assert PLANS_RUN == all_plans
