@@ -330,6 +330,23 @@ int fpq_conv2d_codes_out(const void *x, int x_is_fp32, fpq_format_t fx, float sx
                          int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh, int kw, int stride,
                          int pad, int acc_mode, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- fpq_gemm for callers that cannot allocate device memory ----------------------------------
+ *
+ * For callers that cannot call hipMalloc or hand over a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid allocation.  Same arguments, result and kernels as fpq_gemm, without the
+ * workspace: the scratch memory (activation codes of the fp32 forms, partial sums of the K slices, partial
+ * maxima and scale of the dynamic-scale form) lives in a static device array of FPQ_NOALLOC_SCRATCH_BYTES inside
+ * the library, of which every GPU the library runs on holds its own copy until the process ends.  The call
+ * allocates nothing and frees nothing.  The first call on a device looks the array's address up (make it outside
+ * a graph capture).  A shape whose fpq_gemm_workspace_size exceeds FPQ_NOALLOC_SCRATCH_BYTES returns
+ * FPQ_ERR_WORKSPACE and launches nothing.  All calls on one GPU share that GPU's array: nothing in it has to
+ * start at zero and every call overwrites what it uses, but two calls that overlap in time on one GPU (different
+ * streams, or different host threads on unordered streams) race; order them on one stream. */
+#define FPQ_NOALLOC_SCRATCH_BYTES ((size_t)64 << 20)
+int fpq_gemm_noalloc(const void *x, int x_is_fp32, fpq_format_t fx, float sx, const float *sx_dev,
+                     const void *packed_w, fpq_format_t fw, const float *sw, const float *bias, float *y,
+                     int64_t M, int64_t N, int64_t K, int acc_mode, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

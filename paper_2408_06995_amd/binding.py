@@ -31,6 +31,7 @@ class fpq_plan_t(C.Structure):
 
 
 FPQ_KERNEL_SMALL_TILE, FPQ_KERNEL_256x160, FPQ_KERNEL_128x160, FPQ_KERNEL_ROWS16 = 0, 1, 2, 3
+FPQ_NOALLOC_SCRATCH_BYTES = 64 << 20
 
 
 class FpqError(RuntimeError):
@@ -116,6 +117,8 @@ def lib():
     L.fpq_gemm_plan.argtypes = [i64, i64, i64, C.POINTER(fpq_plan_t)]
     L.fpq_conv2d_plan.restype = i32
     L.fpq_conv2d_plan.argtypes = [i64] * 5 + [i32] * 4 + [C.POINTER(fpq_plan_t)]
+    L.fpq_gemm_noalloc.restype = i32
+    L.fpq_gemm_noalloc.argtypes = [vp, i32, F, fl, f32p, vp, F, f32p, f32p, f32p, i64, i64, i64, i32, vp]
     _lib = L
     return L
 
@@ -126,7 +129,7 @@ EXPORTS = ["fpq_strerror", "fpq_format_max", "fpq_format_check", "fpq_bias_to_sc
            "fpq_conv2d_workspace_size", "fpq_conv2d", "fpq_search_workspace_size", "fpq_search_format",
            "fpq_count_zeros_workspace_size", "fpq_count_zeros", "fpq_gemm_codes_out", "fpq_conv2d_codes_out",
            "fpq_rl_workspace_size", "fpq_rl_init_alpha", "fpq_rl_step", "fpq_rl_mask", "fpq_packed_check", "fpq_rl_im2col",
-           "fpq_gemm_plan", "fpq_conv2d_plan"]
+           "fpq_gemm_plan", "fpq_conv2d_plan", "fpq_gemm_noalloc"]
 
 
 def fmt(f):
@@ -275,6 +278,11 @@ def fpq_gemm(x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, y, M, N, K, a
     wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().fpq_gemm(_ptr(x), int(x_is_fp32), fmt(fx), float(sx), _ptr(sx_dev), _ptr(packed_w), fmt(fw), _ptr(sw),
                           _ptr(bias), _ptr(y), M, N, K, int(acc_mode), _ptr(workspace), wb, _stream()), "fpq_gemm")
+
+
+def fpq_gemm_noalloc(x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, y, M, N, K, acc_mode=FPQ_ACC_FP32):
+    _check(lib().fpq_gemm_noalloc(_ptr(x), int(x_is_fp32), fmt(fx), float(sx), _ptr(sx_dev), _ptr(packed_w), fmt(fw),
+                                  _ptr(sw), _ptr(bias), _ptr(y), M, N, K, int(acc_mode), _stream()), "fpq_gemm_noalloc")
 
 
 def fpq_conv2d(x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, y, B, Cin, H, W, Cout, kh, kw, stride, pad,

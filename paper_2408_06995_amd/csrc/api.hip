@@ -114,6 +114,27 @@ __global__ void write_header_kernel(PackedHeader h, uint32_t* dst)
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Scratch memory of fpq_gemm_noalloc: one copy per GPU the library runs on, held until the process ends.
+// The array's name is only a host-side handle; scratch_on_current_device() asks the runtime for its address on the
+// current device, once per device, and host code uses that pointer everywhere.
+constexpr size_t kStaticScratchBytes = FPQ_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::atomic<void*> g_scratch_ptr[64];
+
+int scratch_on_current_device(void** out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return FPQ_ERR_LAUNCH;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        // two threads may both get here: they receive the same address
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return FPQ_ERR_LAUNCH;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return FPQ_OK;
+}
+
 // Tail of the workspace in dynamic-scale mode: 1024 partial maxima, then [scale, absmax].
 constexpr size_t kDynScaleBytes = 1024 * sizeof(float) + 256;
 
@@ -642,6 +663,21 @@ int fpq_conv2d_codes_out(const void* x, int x_is_fp32, fpq_format_t fx, float sx
     const CodesOut out{fy, sy, sy_dev, yq};
     return run_layer(&out, x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, nullptr, B, Cin, H, W, Cout, kh, kw, stride,
                      pad, 1, acc_mode, workspace, workspace_bytes, stream);
+}
+
+int fpq_gemm_noalloc(const void* x, int x_is_fp32, fpq_format_t fx, float sx, const float* sx_dev, const void* packed_w,
+                     fpq_format_t fw, const float* sw, const float* bias, float* y, int64_t M, int64_t N, int64_t K,
+                     int acc_mode, void* stream)
+{
+    if (M == 0 && N > 0 && K > 0) return FPQ_OK;
+    if (M < 0 || N <= 0 || K <= 0) return FPQ_ERR_SHAPE;
+    // the scratch a call of this shape needs is what fpq_gemm would ask of its caller
+    if (fpq_gemm_workspace_size(M, N, K, x_is_fp32) > kStaticScratchBytes) return FPQ_ERR_WORKSPACE;
+    void* ws = nullptr;
+    const int st = scratch_on_current_device(&ws);
+    if (st) return st;
+    return run_layer(nullptr, x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, y, M, K, 1, 1, N, 1, 1, 1, 0, 0, acc_mode,
+                     ws, kStaticScratchBytes, stream);
 }
 
 }  // extern "C"

@@ -152,4 +152,13 @@ def test_plan_query_and_format_range():
     assert B.fpq_format_check((6, 1, -42, 0.0)) == 0 and B.fpq_format_check((6, 1, -43, 0.0)) == -2
     assert B.fpq_format_max(7, 0, 0) == 0.0
     assert B.fpq_format_check((5, 2, -64, 0.0)) == 0 and B.fpq_format_check((4, 3, -64, 0.0)) == 0
+
+
+def test_noalloc_entry_validates_before_touching_the_gpu():
+    L = B.lib()
+    f = B.fmt(synth.E4M3)
+    p = C.c_void_p(4096)
+    assert L.fpq_gemm_noalloc(p, 1, f, 1.0, None, p, f, p, None, p, 1 << 20, 320, 4096, 0, None) == -6   # 4 GiB of codes
+    assert L.fpq_gemm_noalloc(p, 0, f, 1.0, None, p, f, p, None, p, 0, 8, 32, 0, None) == 0
+    assert L.fpq_gemm_noalloc(p, 0, f, 1.0, None, p, f, p, None, p, 8, 0, 32, 0, None) == -4
     assert L.fpq_strerror(-9).decode().startswith("packed weights")
