@@ -52,6 +52,10 @@ def parse():
     ap.add_argument("--eager", action="store_true",
                     help="launch every step call by call instead of replaying a captured graph (for hardware-counter "
                          "passes of a profiler, where timing does not matter and every dispatch is serialized anyway)")
+    ap.add_argument("--no-grouping", action="store_true",
+                    help="one call per layer also for the layers that the default step hands to fpq_gemm_grouped (the "
+                         "cross-attention key / value projections and the time-embedding projections, which do not "
+                         "depend on the layers between them)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy (the known-size kernel that hardware-counter "
                          "readings of a profiler run are scaled by)")
@@ -123,6 +127,17 @@ def main():
             s.packed[tag], s.sw[tag] = p, sw
         del w, h
         s.scale = torch.empty(2, dtype=torch.float32, device=dev)   # [absmax, scale]
+        # layers that do not depend on the layers between them are handed to the library as one group: all key / value
+        # projections of the cross-attention blocks read the text context, all time-embedding projections of the
+        # residual blocks read the embedding that the two time-embedding layers produce
+        s.group = None
+        if cfg == 5 and not args.no_grouping and L.kind == "linear":
+            if L.name.endswith("attn2.k") or L.name.endswith("attn2.v"):
+                s.group = "context_kv"
+            elif L.name.endswith(".temb"):
+                s.group = "time_embedding"
+        if s.group:
+            s.y_own = torch.empty(L.M * L.N, dtype=torch.float32, device=dev)   # the members' results coexist
         max_y = max(max_y, L.M * L.N)
         max_ws = max(max_ws, ws)
         if L.kind == "conv":
@@ -149,9 +164,28 @@ def main():
             B.fpq_gemm(s.x, xk, FX, 0.0, sdev, s.packed[tag], fw, s.sw[tag], None, y, L.M, L.N, L.K,
                        acc_mode, ws_buf)
 
+    groups = {}
+    for s in states:
+        if s.group:
+            groups.setdefault(s.group, []).append(s)
+    group_args, group_ws = {}, {}
+    for gname, members in groups.items():
+        for tag in ("w8", "w4"):
+            group_args[gname, tag, "fp32"] = B.gemm_problems(
+                [(m.x, None, m.packed[tag], m.sw[tag], None, m.y_own, m.L.M, m.L.N, m.L.K) for m in members])
+        group_ws[gname] = torch.empty(B.fpq_gemm_grouped_workspace_size(group_args[gname, "w8", "fp32"], B.FPQ_X_FP32_DYNAMIC),
+                                      dtype=torch.uint8, device=dev)
+
     def step(acc_mode, static_scale=False):
         for tag, fw in (("w8", FW8), ("w4", FW4)):
+            done = set()
             for s in states:
+                if s.group and not static_scale:
+                    if s.group not in done:      # the whole group at the place of its first member
+                        done.add(s.group)
+                        B.fpq_gemm_grouped(group_args[s.group, tag, "fp32"], B.FPQ_X_FP32_DYNAMIC, FX, fw, acc_mode,
+                                           group_ws[s.group])
+                    continue
                 run_layer(s, tag, fw, acc_mode, static_scale)
 
     flops_step = 2 * sum(synth.flops(L) for L in layers)
@@ -211,10 +245,22 @@ def main():
     def gemm_only(acc_mode):
         n = 0
         for tag, fw in (("w8", FW8), ("w4", FW4)):
+            done = set()
             for s in states:
                 L = s.L
                 buf = codes_bufs[L.name]
                 if buf is None:
+                    continue
+                if s.group:
+                    if s.group not in done:
+                        done.add(s.group)
+                        key = (s.group, tag, "codes")
+                        if key not in group_args:
+                            group_args[key] = B.gemm_problems(
+                                [(codes_bufs[m.L.name], m.scale[1:2], m.packed[tag], m.sw[tag], None, m.y_own, m.L.M, m.L.N,
+                                  m.L.K) for m in groups[s.group]])
+                        B.fpq_gemm_grouped(group_args[key], B.FPQ_X_CODES, FX, fw, acc_mode, None)
+                    n += 1       # counted per layer: the roofline object averages over layers, however they are launched
                     continue
                 if L.kind == "conv":
                     B.fpq_conv2d(buf, 0, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, y, L.B, L.Cin, L.H,
@@ -275,7 +321,8 @@ def main():
         "dtype": "fp8/fp4 codes -> bf16 MFMA, fp32 accumulate" if acc == B.FPQ_ACC_FP32 else "fp8/fp4 MFMA",
         "data": "synthetic",
         "config": {"workload": WORKLOAD_NAMES[args.workload], "layers": len(layers), "flop_per_step": flops_step,
-                   "acc_mode": args.acc},
+                   "acc_mode": args.acc,
+                   "grouped_calls": {g: len(m) for g, m in groups.items()}},
         "roofline": roofline,
     }
 

@@ -330,6 +330,37 @@ int fpq_conv2d_codes_out(const void *x, int x_is_fp32, fpq_format_t fx, float sx
                          int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh, int kw, int stride,
                          int pad, int acc_mode, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- a group of independent linear layers in one call -----------------------------------------
+ *
+ * Several linear layers that do not depend on each other (in the U-Net: the key / value projections of all
+ * cross-attention blocks, which all read the text context, and the time-embedding projections of all residual
+ * blocks) as one call with a handful of launches for the whole group instead of up to three per layer; for layers
+ * this small the launches are what a call costs.  problems is a HOST array of count entries (any count; the
+ * pointers inside are device pointers); it is read during the call only and travels to the device as a kernel
+ * argument, so the call can be captured into a graph.  All problems share the formats fx, fw and acc_mode
+ * (FPQ_ACC_FP32 or FPQ_ACC_FP8_MFMA, no flags).  x_is_fp32:
+ *   FPQ_X_FP32_DYNAMIC  x is fp32 [M, K]; every problem gets its own per-tensor scale absmax(x) / maxval, its codes
+ *                       and its [scale, absmax] are left in the workspace (fpq_gemm_grouped_workspace_size bytes,
+ *                       256-byte aligned, no initialisation: first the codes of every problem, each rounded up to
+ *                       256 bytes, then one 256-byte slot per problem with [scale, absmax] at byte 128);
+ *   FPQ_X_CODES         x holds codes [M, K] with the scale sx_dev[0]; no workspace.
+ * Every K must be a multiple of 16 and every x 16-byte aligned (FPQ_ERR_ALIGN).  Each y[M, N] receives exactly what
+ * fpq_gemm computes for that problem with the register-staged kernel (bit for bit for shapes that fpq_gemm itself
+ * gives to that kernel; the same sums in another order otherwise).  Meant for small problems: every problem runs on
+ * 64 x 64 tiles (or, when all problems of a chunk of 32 have at most 16 rows, on the one-launch kernel for such layers). */
+typedef struct fpq_gemm_problem {
+    const void *x;
+    const float *sx_dev;  /* FPQ_X_CODES only */
+    const void *packed_w; /* from fpq_pack_weights(N, K, 1, 1, fw) */
+    const float *sw;      /* [N] */
+    const float *bias;    /* [N] or NULL */
+    float *y;             /* [M, N] */
+    int64_t M, N, K;
+} fpq_gemm_problem_t;
+size_t fpq_gemm_grouped_workspace_size(const fpq_gemm_problem_t *problems, int count, int x_is_fp32);
+int fpq_gemm_grouped(const fpq_gemm_problem_t *problems, int count, int x_is_fp32, fpq_format_t fx,
+                     fpq_format_t fw, int acc_mode, void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- fpq_gemm for callers that cannot allocate device memory ----------------------------------
  *
  * For callers that cannot call hipMalloc or hand over a workspace: code under HIP graph capture, tight serving

@@ -34,6 +34,11 @@ FPQ_KERNEL_SMALL_TILE, FPQ_KERNEL_256x160, FPQ_KERNEL_128x160, FPQ_KERNEL_ROWS16
 FPQ_NOALLOC_SCRATCH_BYTES = 64 << 20
 
 
+class fpq_gemm_problem_t(C.Structure):
+    _fields_ = [("x", C.c_void_p), ("sx_dev", C.c_void_p), ("packed_w", C.c_void_p), ("sw", C.c_void_p),
+                ("bias", C.c_void_p), ("y", C.c_void_p), ("M", C.c_int64), ("N", C.c_int64), ("K", C.c_int64)]
+
+
 class FpqError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
@@ -117,6 +122,10 @@ def lib():
     L.fpq_gemm_plan.argtypes = [i64, i64, i64, C.POINTER(fpq_plan_t)]
     L.fpq_conv2d_plan.restype = i32
     L.fpq_conv2d_plan.argtypes = [i64] * 5 + [i32] * 4 + [C.POINTER(fpq_plan_t)]
+    L.fpq_gemm_grouped_workspace_size.restype = sz
+    L.fpq_gemm_grouped_workspace_size.argtypes = [C.POINTER(fpq_gemm_problem_t), i32, i32]
+    L.fpq_gemm_grouped.restype = i32
+    L.fpq_gemm_grouped.argtypes = [C.POINTER(fpq_gemm_problem_t), i32, i32, F, F, i32, vp, sz, vp]
     L.fpq_gemm_noalloc.restype = i32
     L.fpq_gemm_noalloc.argtypes = [vp, i32, F, fl, f32p, vp, F, f32p, f32p, f32p, i64, i64, i64, i32, vp]
     _lib = L
@@ -129,7 +138,7 @@ EXPORTS = ["fpq_strerror", "fpq_format_max", "fpq_format_check", "fpq_bias_to_sc
            "fpq_conv2d_workspace_size", "fpq_conv2d", "fpq_search_workspace_size", "fpq_search_format",
            "fpq_count_zeros_workspace_size", "fpq_count_zeros", "fpq_gemm_codes_out", "fpq_conv2d_codes_out",
            "fpq_rl_workspace_size", "fpq_rl_init_alpha", "fpq_rl_step", "fpq_rl_mask", "fpq_packed_check", "fpq_rl_im2col",
-           "fpq_gemm_plan", "fpq_conv2d_plan", "fpq_gemm_noalloc"]
+           "fpq_gemm_plan", "fpq_conv2d_plan", "fpq_gemm_noalloc", "fpq_gemm_grouped_workspace_size", "fpq_gemm_grouped"]
 
 
 def fmt(f):
@@ -278,6 +287,26 @@ def fpq_gemm(x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, y, M, N, K, a
     wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().fpq_gemm(_ptr(x), int(x_is_fp32), fmt(fx), float(sx), _ptr(sx_dev), _ptr(packed_w), fmt(fw), _ptr(sw),
                           _ptr(bias), _ptr(y), M, N, K, int(acc_mode), _ptr(workspace), wb, _stream()), "fpq_gemm")
+
+
+def gemm_problems(items):
+    """[(x, sx_dev or None, packed_w, sw, bias or None, y, M, N, K), ...] of torch tensors -> ctypes array for the
+    grouped call (the tensors must stay alive until the call has been made)."""
+    arr = (fpq_gemm_problem_t * len(items))()
+    for i, (x, sx_dev, packed_w, sw, bias, y, M, N, K) in enumerate(items):
+        arr[i] = fpq_gemm_problem_t(x.data_ptr(), None if sx_dev is None else sx_dev.data_ptr(), packed_w.data_ptr(),
+                                    sw.data_ptr(), None if bias is None else bias.data_ptr(), y.data_ptr(), M, N, K)
+    return arr
+
+
+def fpq_gemm_grouped_workspace_size(problems, x_is_fp32):
+    return lib().fpq_gemm_grouped_workspace_size(problems, len(problems), int(x_is_fp32))
+
+
+def fpq_gemm_grouped(problems, x_is_fp32, fx, fw, acc_mode=FPQ_ACC_FP32, workspace=None):
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().fpq_gemm_grouped(problems, len(problems), int(x_is_fp32), fmt(fx), fmt(fw), int(acc_mode), _ptr(workspace),
+                                  wb, _stream()), "fpq_gemm_grouped")
 
 
 def fpq_gemm_noalloc(x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, y, M, N, K, acc_mode=FPQ_ACC_FP32):

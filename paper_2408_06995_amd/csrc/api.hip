@@ -665,6 +665,109 @@ int fpq_conv2d_codes_out(const void* x, int x_is_fp32, fpq_format_t fx, float sx
                      pad, 1, acc_mode, workspace, workspace_bytes, stream);
 }
 
+// Workspace of the grouped dynamic-scale form: per problem its activation codes (256-byte aligned), then per problem a
+// 256-byte slot [32 partial maxima][scale, absmax].
+static size_t grouped_codes_bytes(const fpq_gemm_problem_t& q) { return align_up((size_t)q.M * (size_t)q.K, 256); }
+
+size_t fpq_gemm_grouped_workspace_size(const fpq_gemm_problem_t* problems, int count, int x_is_fp32)
+{
+    if (!problems || count <= 0 || x_is_fp32 != FPQ_X_FP32_DYNAMIC) return 0;
+    size_t total = 0;
+    for (int i = 0; i < count; ++i) {
+        if (problems[i].M <= 0 || problems[i].K <= 0) return 0;
+        total += grouped_codes_bytes(problems[i]) + 256;
+    }
+    return total;
+}
+
+int fpq_gemm_grouped(const fpq_gemm_problem_t* problems, int count, int x_is_fp32, fpq_format_t fx, fpq_format_t fw,
+                     int acc_mode, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (count == 0) return FPQ_OK;
+    if (!problems) return FPQ_ERR_NULL;
+    if (count < 0) return FPQ_ERR_SHAPE;
+    QParams qx, qw;
+    int st = resolve_format(fx, &qx);
+    if (st) return st;
+    st = resolve_format(fw, &qw);
+    if (st) return st;
+    if (x_is_fp32 != FPQ_X_CODES && x_is_fp32 != FPQ_X_FP32_DYNAMIC) return FPQ_ERR_UNSUPPORTED;
+    if (acc_mode != FPQ_ACC_FP32 && acc_mode != FPQ_ACC_FP8_MFMA) return FPQ_ERR_UNSUPPORTED;   // no flags in the grouped form
+    const bool dyn = x_is_fp32 == FPQ_X_FP32_DYNAMIC;
+    int xkind, wkind;
+    float alpha;
+    st = resolve_kinds(fx, qx.c, fw, qw.c, acc_mode, &xkind, &wkind, &alpha);
+    if (st) return st;
+    for (int i = 0; i < count; ++i) {
+        const fpq_gemm_problem_t& q = problems[i];
+        if (q.M <= 0 || q.N <= 0 || q.K <= 0 || q.M >= (int64_t)1 << 31 || q.N >= (int64_t)1 << 24 || q.K > (1 << 28) ||
+            q.M * q.K >= (int64_t)1 << 31 || q.M * q.N >= (int64_t)1 << 40)
+            return FPQ_ERR_SHAPE;
+        if (!q.x || !q.packed_w || !q.sw || !q.y || (!dyn && !q.sx_dev)) return FPQ_ERR_NULL;
+        if ((q.K & 15) || (reinterpret_cast<uintptr_t>(q.x) & 15) || (reinterpret_cast<uintptr_t>(q.packed_w) & 15) ||
+            (reinterpret_cast<uintptr_t>(q.y) & 3))
+            return FPQ_ERR_ALIGN;
+        const int64_t kpad = padded_k(q.K, 1);
+        if ((is_four_bit(fw) ? kpad / 2 : kpad) * q.N >= (int64_t)1 << 31) return FPQ_ERR_SHAPE;
+    }
+    if (dyn) {
+        if (!workspace || workspace_bytes < fpq_gemm_grouped_workspace_size(problems, count, x_is_fp32)) return FPQ_ERR_WORKSPACE;
+        if (reinterpret_cast<uintptr_t>(workspace) & 255) return FPQ_ERR_ALIGN;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    size_t codes_total = 0;
+    for (int i = 0; i < count; ++i) codes_total += grouped_codes_bytes(problems[i]);
+    uint8_t* codes_at = static_cast<uint8_t*>(workspace);
+    uint8_t* slot_at = codes_at + codes_total;
+    for (int first = 0; first < count; first += kGroupMax) {
+        GroupedArgs g;
+        memset(&g, 0, sizeof g);
+        g.count = count - first < kGroupMax ? count - first : kGroupMax;
+        GemmArgs& a = g.common;
+        a.alpha = alpha;
+        a.H = a.W = a.Ho = a.Wo = 1;
+        a.kh = a.kw = a.stride = 1;
+        a.xkind = xkind; a.wkind = wkind;
+        a.xe = fx.ebits; a.xm = fx.mbits; a.xb = fx.bias;
+        a.we = fw.ebits; a.wm = fw.mbits; a.wb = fw.bias;
+        a.acc_mode = acc_mode;
+        a.splits = 1;
+        a.tile = TILE_GENERIC;
+        for (int i = 0; i < g.count; ++i) {
+            const fpq_gemm_problem_t& q = problems[first + i];
+            GroupedProblem& d = g.p[i];
+            d.wrows = static_cast<const uint8_t*>(q.packed_w) + kPackedRowsOffset;
+            d.sw = q.sw;
+            d.bias = q.bias;
+            d.y = q.y;
+            d.M = (int)q.M; d.N = (int)q.N; d.K = (int)q.K; d.Kpad = (int)padded_k(q.K, 1);
+            if (dyn) {
+                d.x32 = static_cast<const float*>(q.x);
+                d.xcodes = codes_at;
+                d.partials = reinterpret_cast<float*>(slot_at);
+                d.sx_dev = reinterpret_cast<const float*>(slot_at + 128);
+                codes_at += grouped_codes_bytes(q);
+                slot_at += 256;
+            } else {
+                d.xcodes = static_cast<const uint8_t*>(q.x);
+                d.sx_dev = q.sx_dev;
+            }
+        }
+        if (dyn && skinny_grouped_applicable(g)) {
+            // every problem of this chunk has at most 16 rows: maximum, scale, codes and the layer in one launch
+            st = launch_gemm_skinny_dynamic_grouped(g, qx, qx.c, s);
+        } else {
+            if (dyn) {
+                st = launch_quantize_dynamic_grouped(g, qx, qx.c, s);
+                if (st) return st;
+            }
+            st = launch_gemm_grouped(g, s);
+        }
+        if (st) return st;
+    }
+    return FPQ_OK;
+}
+
 int fpq_gemm_noalloc(const void* x, int x_is_fp32, fpq_format_t fx, float sx, const float* sx_dev, const void* packed_w,
                      fpq_format_t fw, const float* sw, const float* bias, float* y, int64_t M, int64_t N, int64_t K,
                      int acc_mode, void* stream)

@@ -105,6 +105,28 @@ struct GemmArgs {
     int act;                // 0, FPQ_ACT_SILU or FPQ_ACT_GEGLU: applied to the fp32 result before it is quantized
 };
 
+// Grouped linear layers (fpq_gemm_grouped): up to kGroupMax independent problems per launch, each launch taking the
+// problems' pointers and sizes as a kernel argument (no copy to the device, so the call can be captured into a graph).
+constexpr int kGroupMax = 32;
+constexpr int kGroupAbsmaxParts = 32;   // partial maxima per problem in the dynamic-scale form
+struct GroupedProblem {
+    const float* x32;       // fp32 activations [M, K] (dynamic-scale form) or null
+    const uint8_t* xcodes;  // activation codes [M, K]: the caller's, or where the grouped quantizer writes them
+    const uint8_t* wrows;   // packed weight rows (after the header)
+    const float* sw;        // [N]
+    const float* bias;      // [N] or null
+    const float* sx_dev;    // device scale of the codes; dynamic-scale form: where [scale, absmax] are published
+    float* y;               // [M, N]
+    float* partials;        // dynamic-scale form: kGroupAbsmaxParts partial maxima
+    int M, N, K, Kpad;      // K = codes per row of x (a multiple of 16), Kpad = packed row length in codes
+};
+struct GroupedArgs {
+    GroupedProblem p[kGroupMax];
+    int count;
+    GemmArgs common;        // formats, operand kinds, alpha, accumulate mode; the per-problem fields are filled in the kernel
+};
+static_assert(sizeof(GroupedArgs) <= 4096, "kernel arguments are limited to 4 KB");
+
 // Kernel family / tile for a problem, and how many K slices share an output tile.
 enum GemmTile : int {
     TILE_GENERIC = 0,    // register-staged 128x128 / 64x64 kernels: any shape
@@ -220,6 +242,11 @@ int launch_gemm(const GemmArgs& a, hipStream_t st);
 // codes [M, K] and publish [scale, absmax] receive what the two-launch form leaves in the workspace).
 int launch_gemm_skinny_dynamic(const GemmArgs& a, const float* x, const QParams& qx, float maxval, uint8_t* codes,
                                float* publish, hipStream_t st);
+// Grouped forms (gemm.hip, quant.hip): one launch each over all problems of g.
+int launch_gemm_grouped(const GroupedArgs& g, hipStream_t st);                 // register-staged 64 x 64 tiles, any shape
+bool skinny_grouped_applicable(const GroupedArgs& g);                           // all problems: at most 16 rows, <= 16 Ki activations
+int launch_gemm_skinny_dynamic_grouped(const GroupedArgs& g, const QParams& qx, float maxval, hipStream_t st);
+int launch_quantize_dynamic_grouped(const GroupedArgs& g, const QParams& qx, float maxval, hipStream_t st);
 bool gemm_dma_applicable(const GemmArgs& a);
 int launch_gemm_dma(const GemmArgs& a, hipStream_t st);
 int launch_gemm_dma_q(const GemmArgs& a, hipStream_t st);   // the same with the result as codes (a.yq)

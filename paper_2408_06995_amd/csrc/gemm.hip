@@ -24,8 +24,9 @@ namespace fpq {
 
 // ---------------------------------------------------------------------------------- the kernel
 
+// The work of one workgroup: output tile number `block` of problem a (smem: the workgroup's dynamic LDS).
 template <int BX, int BW, int WGX, int WGW, int XKIND, int WKIND, int ACC, bool CONV>
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a)
+__device__ __forceinline__ void gemm_tile(const GemmArgs& a, int block, uint8_t* smem)
 {
     constexpr bool W4 = kind_is_4bit(WKIND);
     constexpr int XROWB = 128;                 // bytes of one activation tile row per K step
@@ -49,8 +50,6 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a)
     constexpr bool P4 = kind_is_4bit(PKIND), Q4 = kind_is_4bit(QKIND);
     constexpr int PFMT = mfma_fmt(PKIND), QFMT = mfma_fmt(QKIND);   // immediates of the MFMA
 
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -62,7 +61,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a)
     const int tiles_w = (a.N + BW - 1) / BW;
     const int tiles_x = (a.M + BX - 1) / BX;
     const int ntiles = tiles_w * tiles_x;
-    int bid = blockIdx.x;
+    int bid = block;
     {
         const int per = ntiles >> 3;
         if (bid < (per << 3)) bid = (bid & 7) * per + (bid >> 3);
@@ -386,6 +385,40 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a)
         store_all(std::false_type{});
 }
 
+template <int BX, int BW, int WGX, int WGW, int XKIND, int WKIND, int ACC, bool CONV>
+__global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    gemm_tile<BX, BW, WGX, WGW, XKIND, WKIND, ACC, CONV>(a, blockIdx.x, smem);
+}
+
+// Grouped linear layers: blockIdx.y picks the problem, blockIdx.x the output tile within it (the grid is as wide as
+// the problem with the most tiles; workgroups beyond a problem's own tile count leave at once).
+__device__ __forceinline__ GemmArgs grouped_problem_args(const GroupedArgs& g, int pi)
+{
+    GemmArgs a = g.common;
+    const GroupedProblem& q = g.p[pi];
+    a.x = q.xcodes;
+    a.wrows = q.wrows;
+    a.sw = q.sw;
+    a.bias = q.bias;
+    a.sx_dev = q.sx_dev;
+    a.y = q.y;
+    a.M = q.M; a.N = q.N; a.Kpad = q.Kpad; a.Kreal = q.K;
+    a.B = q.M; a.H = 1; a.W = 1; a.Cp = q.K; a.Ho = 1; a.Wo = 1;
+    return a;
+}
+
+template <int XKIND, int WKIND, int ACC>
+__global__ __launch_bounds__(256) void gemm_grouped_kernel(const GroupedArgs g)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    const GemmArgs a = grouped_problem_args(g, blockIdx.y);
+    const int tiles = ((a.M + 63) / 64) * ((a.N + 63) / 64);
+    if ((int)blockIdx.x >= tiles) return;
+    gemm_tile<64, 64, 2, 2, XKIND, WKIND, ACC, false>(a, blockIdx.x, smem);
+}
+
 // ---------------------------------------------------------------------------------- dispatch
 
 template <int BX, int BW, int WGX, int WGW, int XKIND, int WKIND, int ACC, bool CONV>
@@ -495,9 +528,9 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const GemmArgs a)
 // quantizer's and the layer's.  The weight loads of the first round go out before the activations are touched.
 // Codes, scale, K split and summation order are those of the two-launch form, so the result is bit-identical.
 template <int WKIND>
-__global__ __launch_bounds__(256) void gemm_skinny_dynamic_kernel(const GemmArgs a, const float4* __restrict__ x4, int n4,
-                                                                  QParams qx, float maxval, uint32_t* __restrict__ codes_out,
-                                                                  float* __restrict__ publish)
+__device__ __forceinline__ void gemm_skinny_dynamic_block(const GemmArgs& a, int block, const float4* __restrict__ x4, int n4,
+                                                          const QParams& qx, float maxval, uint32_t* __restrict__ codes_out,
+                                                          float* __restrict__ publish)
 {
     constexpr bool W4 = kind_is_4bit(WKIND);
     constexpr int U = 5;
@@ -506,7 +539,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_dynamic_kernel(const GemmArgs
     __shared__ __attribute__((aligned(16))) uint8_t xcodes[16384];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r16 = lane & 15, kq = lane >> 4;
-    const int n0 = blockIdx.x * 16;
+    const int n0 = block * 16;
     const int K = a.Kreal;
     const int nsteps = (K + 63) / 64;
     const bool has_m = r16 < a.M, has_n = n0 + r16 < a.N;
@@ -548,10 +581,10 @@ __global__ __launch_bounds__(256) void gemm_skinny_dynamic_kernel(const GemmArgs
             const uint32_t c2 = quantize_nearest(v[e].z, rx, qx), c3 = quantize_nearest(v[e].w, rx, qx);
             const uint32_t word = c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
             reinterpret_cast<uint32_t*>(xcodes)[i] = word;
-            if (blockIdx.x == 0) codes_out[i] = word;      // the first workgroup leaves codes and scale where the
+            if (block == 0) codes_out[i] = word;      // the first workgroup leaves codes and scale where the
         }                                                  // two-launch form does, for inspection
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if (block == 0 && threadIdx.x == 0) {
         publish[0] = sx;
         publish[1] = m;
     }
@@ -595,6 +628,25 @@ __global__ __launch_bounds__(256) void gemm_skinny_dynamic_kernel(const GemmArgs
     }
 }
 
+template <int WKIND>
+__global__ __launch_bounds__(256) void gemm_skinny_dynamic_kernel(const GemmArgs a, const float4* __restrict__ x4, int n4,
+                                                                  QParams qx, float maxval, uint32_t* __restrict__ codes_out,
+                                                                  float* __restrict__ publish)
+{
+    gemm_skinny_dynamic_block<WKIND>(a, blockIdx.x, x4, n4, qx, maxval, codes_out, publish);
+}
+
+// The same for a group of such layers in one launch: blockIdx.y picks the problem.
+template <int WKIND>
+__global__ __launch_bounds__(256) void gemm_skinny_dynamic_grouped_kernel(const GroupedArgs g, QParams qx, float maxval)
+{
+    const GemmArgs a = grouped_problem_args(g, blockIdx.y);
+    if ((int)blockIdx.x * 16 >= a.N) return;
+    const GroupedProblem& q = g.p[blockIdx.y];
+    gemm_skinny_dynamic_block<WKIND>(a, blockIdx.x, reinterpret_cast<const float4*>(q.x32), (a.M * a.Kreal) >> 2, qx, maxval,
+                                     reinterpret_cast<uint32_t*>(const_cast<uint8_t*>(q.xcodes)), const_cast<float*>(q.sx_dev));
+}
+
 static bool skinny_applicable(const GemmArgs& a)
 {
     return !a.conv_out && a.M <= 16 && a.acc_mode == FPQ_ACC_FP32 && a.xkind == OPK_FP8 &&
@@ -617,6 +669,61 @@ int launch_gemm_skinny_dynamic(const GemmArgs& a, const float* x, const QParams&
         hipLaunchKernelGGL(gemm_skinny_dynamic_kernel<OPK_FP4>, grid, dim3(256), 0, st, a, reinterpret_cast<const float4*>(x),
                            (int)(n >> 2), qx, maxval, reinterpret_cast<uint32_t*>(codes), publish);
     return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
+}
+
+// ---------------------------------------------------------------------------------- grouped linear layers
+
+bool skinny_grouped_applicable(const GroupedArgs& g)
+{
+    const GemmArgs& c = g.common;
+    if (c.acc_mode != FPQ_ACC_FP32 || c.xkind != OPK_FP8 || (c.wkind != OPK_FP8 && c.wkind != OPK_FP4)) return false;
+    for (int i = 0; i < g.count; ++i) {
+        const GroupedProblem& q = g.p[i];
+        if (q.M > 16 || !q.x32 || (size_t)q.M * q.K > 16384 || (q.K & 15) || (reinterpret_cast<uintptr_t>(q.x32) & 15))
+            return false;
+    }
+    return true;
+}
+
+int launch_gemm_skinny_dynamic_grouped(const GroupedArgs& g, const QParams& qx, float maxval, hipStream_t st)
+{
+    int maxn = 0;
+    for (int i = 0; i < g.count; ++i) maxn = g.p[i].N > maxn ? g.p[i].N : maxn;
+    const dim3 grid((unsigned)((maxn + 15) / 16), (unsigned)g.count);
+    if (g.common.wkind == OPK_FP8)
+        hipLaunchKernelGGL(gemm_skinny_dynamic_grouped_kernel<OPK_FP8>, grid, dim3(256), 0, st, g, qx, maxval);
+    else
+        hipLaunchKernelGGL(gemm_skinny_dynamic_grouped_kernel<OPK_FP4>, grid, dim3(256), 0, st, g, qx, maxval);
+    return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
+}
+
+template <int XKIND, int WKIND, int ACC>
+static int launch_grouped_one(const GroupedArgs& g, hipStream_t st)
+{
+    constexpr int WROWB = kind_is_4bit(WKIND) ? 64 : 128;
+    constexpr int smem = 2 * (64 * 128 + 64 * WROWB);
+    int maxt = 0;
+    for (int i = 0; i < g.count; ++i) {
+        const int t = ((g.p[i].M + 63) / 64) * ((g.p[i].N + 63) / 64);
+        maxt = t > maxt ? t : maxt;
+    }
+    hipLaunchKernelGGL((gemm_grouped_kernel<XKIND, WKIND, ACC>), dim3((unsigned)maxt, (unsigned)g.count), dim3(256), smem, st, g);
+    return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
+}
+
+int launch_gemm_grouped(const GroupedArgs& g, hipStream_t st)
+{
+    const GemmArgs& a = g.common;
+    if (g.count <= 0) return FPQ_OK;
+    if (a.acc_mode == FPQ_ACC_FP8_MFMA) {
+        if (a.xkind == OPK_FP8 && a.wkind == OPK_FP8) return launch_grouped_one<OPK_FP8, OPK_FP8, FPQ_ACC_FP8_MFMA>(g, st);
+        if (a.xkind == OPK_FP8 && a.wkind == OPK_FP4) return launch_grouped_one<OPK_FP8, OPK_FP4, FPQ_ACC_FP8_MFMA>(g, st);
+        return FPQ_ERR_UNSUPPORTED;
+    }
+    if (a.xkind == OPK_FP8 && a.wkind == OPK_FP8) return launch_grouped_one<OPK_FP8, OPK_FP8, FPQ_ACC_FP32>(g, st);
+    if (a.xkind == OPK_FP8 && a.wkind == OPK_FP4) return launch_grouped_one<OPK_FP8, OPK_FP4, FPQ_ACC_FP32>(g, st);
+    if (kind_is_4bit(a.wkind)) return launch_grouped_one<OPK_GENERIC8, OPK_GENERIC4, FPQ_ACC_FP32>(g, st);
+    return launch_grouped_one<OPK_GENERIC8, OPK_GENERIC8, FPQ_ACC_FP32>(g, st);
 }
 
 int launch_gemm(const GemmArgs& a, hipStream_t st)

@@ -326,6 +326,61 @@ int launch_quantize_dynamic_small(const float* x, size_t n, const QParams& q, fl
     return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
 }
 
+// ------------------------------------------------------------------- grouped dynamic-scale quantizer
+
+// Dynamic per-tensor scales of a group of activation tensors in two launches for the whole group (blockIdx.y picks the
+// problem): per-block partial maxima of |x|, then every block of the second kernel folds its problem's partials into
+// scale = absmax / maxval (the same arithmetic as the single-tensor form, so the codes are the same bit for bit),
+// block 0 of a problem publishes [scale, absmax] where the layer kernel reads its scale, and the elements are encoded.
+// Each tensor has a multiple of 16 elements and is 16-byte aligned (rows of K % 16 == 0 codes).
+__global__ __launch_bounds__(256) void absmax_grouped_kernel(const GroupedArgs g)
+{
+    const GroupedProblem& q = g.p[blockIdx.y];
+    const float4* x4 = reinterpret_cast<const float4*>(q.x32);
+    const int n4 = (q.M * q.K) >> 2;
+    float v = 0.0f;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < n4; i += kGroupAbsmaxParts * 256) v = max4(v, x4[i]);
+    v = block_max(v);
+    if (threadIdx.x == 0) q.partials[blockIdx.x] = v;
+}
+
+__global__ __launch_bounds__(256) void quantize_grouped_kernel(const GroupedArgs g, QParams qx, float maxval)
+{
+    const GroupedProblem& q = g.p[blockIdx.y];
+    float v = threadIdx.x < kGroupAbsmaxParts ? q.partials[threadIdx.x] : 0.0f;
+    v = block_max(v);
+    const float sc = (v == 0.0f) ? 1.0f : __fdiv_rn(v, maxval);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        float* pub = const_cast<float*>(q.sx_dev);
+        pub[0] = sc;
+        pub[1] = v;
+    }
+    const float r = __fdiv_rn(1.0f, sc);
+    const float4* x4 = reinterpret_cast<const float4*>(q.x32);
+    uint32_t* codes = reinterpret_cast<uint32_t*>(const_cast<uint8_t*>(q.xcodes));
+    const int n4 = (q.M * q.K) >> 2;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < n4; i += gridDim.x * 256) {
+        const float4 a = x4[i];
+        codes[i] = quantize_nearest(a.x, r, qx) | (quantize_nearest(a.y, r, qx) << 8) | (quantize_nearest(a.z, r, qx) << 16) |
+                   (quantize_nearest(a.w, r, qx) << 24);
+    }
+}
+
+int launch_quantize_dynamic_grouped(const GroupedArgs& g, const QParams& qx, float maxval, hipStream_t st)
+{
+    if (g.count <= 0) return FPQ_OK;
+    size_t most = 0;
+    for (int i = 0; i < g.count; ++i) {
+        const size_t n4 = ((size_t)g.p[i].M * g.p[i].K) >> 2;
+        most = n4 > most ? n4 : most;
+    }
+    hipLaunchKernelGGL(absmax_grouped_kernel, dim3(kGroupAbsmaxParts, (unsigned)g.count), dim3(256), 0, st, g);
+    size_t gx = (most + 1023) / 1024;          // four 16-byte loads per lane
+    gx = gx < 1 ? 1 : (gx > 256 ? 256 : gx);
+    hipLaunchKernelGGL(quantize_grouped_kernel, dim3((unsigned)gx, (unsigned)g.count), dim3(256), 0, st, g, qx, maxval);
+    return hipGetLastError() == hipSuccess ? FPQ_OK : FPQ_ERR_LAUNCH;
+}
+
 // ------------------------------------------------------------------- quantize NCHW -> NHWC codes
 
 // One block turns a 64-channel x 64-pixel patch of one image: reads run along pixels (contiguous in
