@@ -270,6 +270,59 @@ def requantize_bounds(Y, T, fmt, scale, rel, abs_):
     return quantize(lo, fmt, scale), quantize(hi, fmt, scale)
 
 
+def prune_2of4(codes, fmt):
+    """Structured sparsity for the weight operand (Section VI, "Sparsity", and the future work of Section VIII: use the
+    zeros that quantization produces).  codes: weight codes [N, Cin] or [N, Cin, kh, kw].  The input channels of every
+    output channel and kernel tap are taken in groups of four consecutive ones (the last group of a channel count that
+    is not a multiple of four is completed with zeros); in each group the two codes of largest magnitude are kept, the
+    other two become code 0.  Equal magnitudes: the lower channel index wins.  A group that has at most two non-zero
+    codes to begin with, which is what quantization to few bits makes common, is unchanged.
+    Returns (pruned codes, same shape; number of groups that lost a non-zero value)."""
+    e, m, b, _ = fmt
+    codes = _u8(codes)
+    shape = codes.shape
+    c4 = codes.reshape(shape[0], shape[1], -1)                      # [N, Cin, taps]
+    N, Cin, taps = c4.shape
+    mag = np.array([decode(fmt, k) for k in range(1 << (e + m))])   # magnitude of every code without its sign bit
+    out = c4.copy()
+    altered = 0
+    for n in range(N):
+        for t in range(taps):
+            for c0 in range(0, Cin, 4):
+                grp = list(range(c0, min(c0 + 4, Cin)))
+                mags = [mag[int(c4[n, c, t]) & ((1 << (e + m)) - 1)] for c in grp]
+                order = sorted(range(len(grp)), key=lambda i: (-mags[i], i))   # largest first, lower index first among equals
+                keep = set(order[:2])
+                lost = False
+                for i, c in enumerate(grp):
+                    if i not in keep:
+                        lost = lost or mags[i] != 0.0
+                        out[n, c, t] = 0
+                altered += int(lost)
+    return out.reshape(shape), altered
+
+
+def prune_2of4_fast(codes, fmt):
+    """The same rule vectorised with numpy (stable sort on the negated magnitudes), for tensors the loop above is too
+    slow for; the tests check it against the loop."""
+    e, m, b, _ = fmt
+    codes = _u8(codes)
+    shape = codes.shape
+    c4 = codes.reshape(shape[0], shape[1], -1)
+    N, Cin, taps = c4.shape
+    pad = (-Cin) % 4
+    g = np.concatenate([c4, np.zeros((N, pad, taps), dtype=np.uint8)], axis=1) if pad else c4
+    g = g.transpose(0, 2, 1).reshape(N, taps, -1, 4)                # [N, taps, groups, 4]
+    mag = np.array([decode(fmt, k) for k in range(1 << (e + m))])[g & ((1 << (e + m)) - 1)]
+    order = np.argsort(-mag, axis=-1, kind="stable")                # largest first; equal magnitudes keep index order
+    drop = order[..., 2:]
+    pruned = g.copy()
+    np.put_along_axis(pruned, drop, 0, axis=-1)
+    altered = int((np.take_along_axis(mag, drop, axis=-1) != 0).any(axis=-1).sum())
+    pruned = pruned.reshape(N, taps, -1).transpose(0, 2, 1)[:, :Cin, :]
+    return np.ascontiguousarray(pruned).reshape(shape), altered
+
+
 def count_zeros(values):
     """Section VI, "Sparsity": the number of values of a tensor that are zero (+0 and -0 alike)."""
     return int(np.count_nonzero(np.asarray(values) == 0))
