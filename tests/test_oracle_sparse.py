@@ -47,7 +47,7 @@ def test_every_group_of_four_e2m1_codes_keeps_a_pair_of_largest_total_magnitude(
 def test_ties_go_to_the_lower_channel_and_dropped_codes_become_plus_zero():
     one, two, neg_one = 2, 4, 2 | 8              # E2M1 (bias 1): code 2 = 1.0, code 4 = 2.0, sign bit = 8
     cases = [([one, one, one, one], [one, one, 0, 0]), ([0, two, two, two], [0, two, two, 0]),
-             ([neg_one, one, two, one], [neg_one, 0, two, 0]), ([one, 0, 0, 8], [one, 0, 0, 8]),   # -0 counts as zero, kept as is
+             ([neg_one, one, two, one], [neg_one, 0, two, 0]), ([one, 0, 0, 8], [one, 0, 0, 0]),   # -0 counts as zero; not among the two kept, it becomes +0
              ([two, one, one, two], [two, 0, 0, two])]
     for src, want in cases:
         got, _ = oracle.prune_2of4(np.array([src], dtype=np.uint8), E2M1)
