@@ -30,10 +30,10 @@ PEAK_FP8_TFLOPS = 5000.0    # MI355X dense fp8 MFMA (also the rate of fp8 x fp4)
 PEAK_HBM_GBS = 8000.0
 ALU_LANE_RATE = 256 * 4 * 16 * 2.4e9   # vector instructions per lane and second: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
 SEARCH_OPS = 11                        # vector instructions per element and candidate in the search kernel's inner loop
-# HBM-side bytes per layer launch from the two hardware-counter passes whose summary is
-# profiles/cfg5_step_hbm_traffic_pmc.txt (30.50 MB fetched + 36.39 MB written, the split-K reductions included); a profiler figure, not
-# measurable from inside this script, hence only for the workload and mode it was taken on.
-MEASURED_TRAFFIC = {("cfg5", "fp32"): 68.99e6}
+# HBM-side bytes per layer launch from two hardware-counter passes of a profiler (FETCH_SIZE, then WRITE_SIZE, the
+# split-K reductions included): not measurable from inside this script, hence a constant, valid only for the workload,
+# accumulate mode and call structure it was taken on; the summary file named here holds the command and the arithmetic.
+MEASURED_TRAFFIC = {}
 
 
 def parse():
@@ -56,6 +56,11 @@ def parse():
                     help="one call per layer also for the layers that the default step hands to fpq_gemm_grouped (the "
                          "cross-attention key / value projections and the time-embedding projections, which do not "
                          "depend on the layers between them)")
+    ap.add_argument("--layer-kernels-only", action="store_true",
+                    help="for hardware-counter passes of a profiler: set up, then launch every GEMM / conv call of one "
+                         "step (the launches the roofline object is about) exactly --steps times, call by call, and "
+                         "exit; nothing else of the benchmark runs, so per-launch counter figures are the profiler's "
+                         "sums over the layer kernels divided by steps x layers")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy (the known-size kernel that hardware-counter "
                          "readings of a profiler run are scaled by)")
@@ -220,7 +225,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    sec = timed(acc, args.steps, args.warmup)
+    sec = None if args.layer_kernels_only else timed(acc, args.steps, args.warmup)
 
     # ---- the GEMM kernels alone: every layer's activation codes are prepared first (untimed), then all GEMM /
     # conv launches of one step (and the split-K reductions that belong to them) are captured into one graph
@@ -294,6 +299,14 @@ def main():
         tot_fl = 2 * sum(synth.flops(s.L) for s in states if codes_bufs[s.L.name] is not None)
         return tot_ms, tot_fl, nlaunch, {}
 
+    if args.layer_kernels_only:
+        prepare_codes()
+        for _ in range(args.steps):
+            n_layers = gemm_only(acc)
+        torch.cuda.synchronize()
+        print(json.dumps({"layer_kernels_only": True, "executions": args.steps, "layers_per_execution": n_layers,
+                          "acc_mode": args.acc, "grouped_calls": {g: len(m) for g, m in groups.items()}}))
+        return
     g_ms, g_fl, g_n, per_layer = gemm_breakdown(acc)
     # algorithmic bytes of those launches: activation codes once (not the im2col expansion), packed weights, fp32 output
     alg_bytes = 0
@@ -304,9 +317,14 @@ def main():
         alg_bytes += 2 * (codes_bufs[L.name].numel() + 4 * L.M * L.N) + s.packed["w8"].numel() + s.packed["w4"].numel()
     peak = PEAK_BF16_TFLOPS if acc == B.FPQ_ACC_FP32 else PEAK_FP8_TFLOPS
     achieved = g_fl / (g_ms * 1e-3) / 1e12
+    traffic = MEASURED_TRAFFIC.get((args.workload, args.acc, "grouped" if groups else "one call per layer"))
     roofline = {"bound": "mfma", "kernel": "fpq::gemm_dma_kernel / gemm_kernel (all GEMM and conv launches of one step, one graph)", "achieved": round(achieved, 2),
                 "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                "traffic": MEASURED_TRAFFIC.get((args.workload, args.acc)),
+                # the target of this workload is stated against the 8-bit matrix peak, which the exact (fp32-accumulate)
+                # mode cannot use: its products go through the bf16 matrix instruction, whose peak is half of it
+                "frac_of_fp8_peak": round(achieved / PEAK_FP8_TFLOPS, 4),
+                "traffic": None if traffic is None else traffic["bytes_per_launch"],
+                "traffic_source": None if traffic is None else traffic["source"],
                 "traffic_unit": "bytes per launch (L2 <-> fabric, rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, "
                                 "factors from a 256 MiB copy kernel)",
                 "algorithmic_bytes_per_launch": round(alg_bytes / g_n),
@@ -497,6 +515,31 @@ def main():
             singles[cname] = entry
             del xs, w, cb, yb, yq, wsb
         out["single_layers"] = singles
+        # what the part sustains on the bare matrix instructions and on a plain copy (probe kernels of the library)
+        pk = {}
+        pdst = torch.empty(2048 * 256, dtype=torch.float32, device=dev)
+        for name, kind, iters in (("bf16_mfma_TFLOP/s", B.FPQ_PROBE_MFMA_BF16, 1500), ("fp8_mfma_TFLOP/s", B.FPQ_PROBE_MFMA_FP8, 1500)):
+            B.fpq_probe_peak(kind, 100, None, pdst)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            work = sum(B.fpq_probe_peak(kind, iters, None, pdst) for _ in range(3))
+            e1.record()
+            e1.synchronize()
+            pk[name] = round(work / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+        csrc = [torch.empty(128 << 20, dtype=torch.float32, device=dev).normal_() for _ in range(2)]   # 512 MiB each
+        cdst = [torch.empty(128 << 20, dtype=torch.float32, device=dev) for _ in range(2)]
+        B.fpq_probe_peak(B.FPQ_PROBE_COPY, 1, csrc[0], cdst[0])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        work = sum(B.fpq_probe_peak(B.FPQ_PROBE_COPY, 1, csrc[i & 1], cdst[i & 1]) for i in range(8))
+        e1.record()
+        e1.synchronize()
+        pk["copy_GB/s_read_plus_write"] = round(work / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+        del csrc, cdst
+        pk["note"] = ("register-only MFMA loops with operands that change every instruction, and a 512 MiB device copy; "
+                      "the nominal peaks are %g / %g TFLOP/s and %g GB/s" % (PEAK_BF16_TFLOPS, PEAK_FP8_TFLOPS, PEAK_HBM_GBS))
+        roofline["measured_peak"] = pk
+        roofline["frac_of_measured_peak"] = round(achieved / pk["bf16_mfma_TFLOP/s" if acc == B.FPQ_ACC_FP32 else "fp8_mfma_TFLOP/s"], 4)
         # encoding / bias search of Section V-A on one activation tensor (8 x 320 x 64 x 64): 4 FP8 encodings x 111
         # bias candidates; bound by vector ALU work: 11 vector instructions per element and candidate (SEARCH_OPS) against the lane-instruction rate of the chip
         xs = synth.activations_torch((8, 320, 64, 64), 3, dev).reshape(-1)

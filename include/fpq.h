@@ -330,6 +330,37 @@ int fpq_conv2d_codes_out(const void *x, int x_is_fp32, fpq_format_t fx, float sx
                          int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh, int kw, int stride,
                          int pad, int acc_mode, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- structured-sparse weight operand (Section VI, "Sparsity") ----------------------------------
+ *
+ * Quantization to few bits turns many weights into zero (the paper measures up to 617 times more zeros in FP4 than in
+ * full precision) and names the use of that sparsity as the next step.  These entry points store and multiply the
+ * weight operand in the 2-of-4 form that the matrix unit's sparse instructions take: of every four consecutive input
+ * channels (per output channel and kernel tap; a channel count that is not a multiple of four is completed with zeros)
+ * the two codes of largest magnitude are kept (equal magnitudes: the lower channel), the other two are dropped.  A
+ * group with at most two non-zero codes loses nothing, so a weight tensor whose groups are all like that gives
+ * exactly the dense layer; *dropped_out counts the groups that lost a non-zero code.
+ *
+ * fpq_pack_weights_sparse: arguments as fpq_pack_weights (same per-channel scales, same Eq. (12) / Eq. (8) codes);
+ *   packed receives fpq_packed_sparse_size bytes, 256-byte aligned (header; kept codes, half the bytes of the dense
+ *   form; one 2-bit position per kept code); codes_out, if not NULL, the pruned codes [N, Cin, kh, kw] one per byte
+ *   (dropped entries are code 0); dropped_out one 64-bit count in device memory.
+ * fpq_gemm_sparse / fpq_conv2d_sparse: as fpq_gemm / fpq_conv2d with FPQ_ACC_FP32 on such a buffer: every kept
+ *   product is formed exactly and summed in fp32, so the result is the dense layer on the pruned codes within
+ *   1e-5 * sum|a_k b_k| + 1e-6.  Activations in the hardware's E4M3 encoding ((4, 3, b) with max value up to
+ *   448 * 2^(7 - b)), weights E4M3 or E2M1; other formats return FPQ_ERR_UNSUPPORTED.  workspace: the size the dense
+ *   call states for the same x_is_fp32 (only the activation codes and the dynamic-scale slot are used). */
+size_t fpq_packed_sparse_size(int64_t N, int64_t Cin, int kh, int kw, fpq_format_t f);
+int fpq_pack_weights_sparse(const float *w, int64_t N, int64_t Cin, int kh, int kw, fpq_format_t f,
+                            const float *scale, const uint8_t *mask, void *packed, size_t packed_bytes,
+                            float *scale_out, uint8_t *codes_out, uint64_t *dropped_out, void *stream);
+int fpq_gemm_sparse(const void *x, int x_is_fp32, fpq_format_t fx, float sx, const float *sx_dev,
+                    const void *packed_sparse, fpq_format_t fw, const float *sw, const float *bias, float *y,
+                    int64_t M, int64_t N, int64_t K, void *workspace, size_t workspace_bytes, void *stream);
+int fpq_conv2d_sparse(const void *x, int x_is_fp32, fpq_format_t fx, float sx, const float *sx_dev,
+                      const void *packed_sparse, fpq_format_t fw, const float *sw, const float *bias, float *y,
+                      int64_t B, int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh, int kw, int stride,
+                      int pad, void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- a group of independent linear layers in one call -----------------------------------------
  *
  * Several linear layers that do not depend on each other (in the U-Net: the key / value projections of all
@@ -360,6 +391,20 @@ typedef struct fpq_gemm_problem {
 size_t fpq_gemm_grouped_workspace_size(const fpq_gemm_problem_t *problems, int count, int x_is_fp32);
 int fpq_gemm_grouped(const fpq_gemm_problem_t *problems, int count, int x_is_fp32, fpq_format_t fx,
                      fpq_format_t fw, int acc_mode, void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---- machine-ceiling probes (for the benchmark's roofline object) -------------------------------
+ *
+ * What this GPU sustains with nothing but the instruction in question in the loop, to set beside the published peaks
+ * that roofline fractions are quoted against.  kind:
+ *   FPQ_PROBE_MFMA_BF16  register-only loop of the bf16 matrix instruction of the fp32-accumulate mode, operands
+ *                        that change with every instruction; dst receives 2048 * 256 floats (bytes = size of dst);
+ *   FPQ_PROBE_MFMA_FP8   the same with the 8-bit matrix instruction of FPQ_ACC_FP8_MFMA;
+ *   FPQ_PROBE_COPY       dst[0 .. bytes) = src[0 .. bytes), 16-byte aligned.
+ * One launch on stream; work_out (host) receives the flops (MFMA kinds) or the bytes read plus written (copy) of
+ * that launch, for the caller to divide by the time it measures. */
+typedef enum fpq_probe_kind { FPQ_PROBE_MFMA_BF16 = 0, FPQ_PROBE_MFMA_FP8 = 1, FPQ_PROBE_COPY = 2 } fpq_probe_kind;
+int fpq_probe_peak(int kind, int iterations, const void *src, void *dst, size_t bytes, double *work_out,
+                   void *stream);
 
 /* ---- fpq_gemm for callers that cannot allocate device memory ----------------------------------
  *

@@ -126,6 +126,16 @@ def lib():
     L.fpq_gemm_grouped_workspace_size.argtypes = [C.POINTER(fpq_gemm_problem_t), i32, i32]
     L.fpq_gemm_grouped.restype = i32
     L.fpq_gemm_grouped.argtypes = [C.POINTER(fpq_gemm_problem_t), i32, i32, F, F, i32, vp, sz, vp]
+    L.fpq_packed_sparse_size.restype = sz
+    L.fpq_packed_sparse_size.argtypes = [i64, i64, i32, i32, F]
+    L.fpq_pack_weights_sparse.restype = i32
+    L.fpq_pack_weights_sparse.argtypes = [f32p, i64, i64, i32, i32, F, f32p, u8p, vp, sz, f32p, u8p, vp, vp]
+    L.fpq_gemm_sparse.restype = i32
+    L.fpq_gemm_sparse.argtypes = [vp, i32, F, fl, f32p, vp, F, f32p, f32p, f32p, i64, i64, i64, vp, sz, vp]
+    L.fpq_conv2d_sparse.restype = i32
+    L.fpq_conv2d_sparse.argtypes = ([vp, i32, F, fl, f32p, vp, F, f32p, f32p, f32p] + [i64] * 5 + [i32] * 4 + [vp, sz, vp])
+    L.fpq_probe_peak.restype = i32
+    L.fpq_probe_peak.argtypes = [i32, i32, vp, vp, sz, C.POINTER(C.c_double), vp]
     L.fpq_gemm_noalloc.restype = i32
     L.fpq_gemm_noalloc.argtypes = [vp, i32, F, fl, f32p, vp, F, f32p, f32p, f32p, i64, i64, i64, i32, vp]
     _lib = L
@@ -138,7 +148,8 @@ EXPORTS = ["fpq_strerror", "fpq_format_max", "fpq_format_check", "fpq_bias_to_sc
            "fpq_conv2d_workspace_size", "fpq_conv2d", "fpq_search_workspace_size", "fpq_search_format",
            "fpq_count_zeros_workspace_size", "fpq_count_zeros", "fpq_gemm_codes_out", "fpq_conv2d_codes_out",
            "fpq_rl_workspace_size", "fpq_rl_init_alpha", "fpq_rl_step", "fpq_rl_mask", "fpq_packed_check", "fpq_rl_im2col",
-           "fpq_gemm_plan", "fpq_conv2d_plan", "fpq_gemm_noalloc", "fpq_gemm_grouped_workspace_size", "fpq_gemm_grouped"]
+           "fpq_gemm_plan", "fpq_conv2d_plan", "fpq_gemm_noalloc", "fpq_gemm_grouped_workspace_size", "fpq_gemm_grouped", "fpq_probe_peak",
+           "fpq_packed_sparse_size", "fpq_pack_weights_sparse", "fpq_gemm_sparse", "fpq_conv2d_sparse"]
 
 
 def fmt(f):
@@ -307,6 +318,44 @@ def fpq_gemm_grouped(problems, x_is_fp32, fx, fw, acc_mode=FPQ_ACC_FP32, workspa
     wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().fpq_gemm_grouped(problems, len(problems), int(x_is_fp32), fmt(fx), fmt(fw), int(acc_mode), _ptr(workspace),
                                   wb, _stream()), "fpq_gemm_grouped")
+
+
+def fpq_packed_sparse_size(N, Cin, kh, kw, f):
+    return lib().fpq_packed_sparse_size(N, Cin, kh, kw, fmt(f))
+
+
+def fpq_pack_weights_sparse(w, f, scale, mask, packed, scale_out, codes_out, dropped_out):
+    """dropped_out: int64 tensor of one element."""
+    N, Cin = w.shape[0], w.shape[1]
+    kh, kw = (w.shape[2], w.shape[3]) if w.dim() == 4 else (1, 1)
+    _check(lib().fpq_pack_weights_sparse(_ptr(w), N, Cin, kh, kw, fmt(f), _ptr(scale), _ptr(mask), _ptr(packed),
+                                         packed.numel() * packed.element_size(), _ptr(scale_out), _ptr(codes_out),
+                                         _ptr(dropped_out), _stream()), "fpq_pack_weights_sparse")
+
+
+def fpq_gemm_sparse(x, x_is_fp32, fx, sx, sx_dev, packed_sparse, fw, sw, bias, y, M, N, K, workspace=None):
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().fpq_gemm_sparse(_ptr(x), int(x_is_fp32), fmt(fx), float(sx), _ptr(sx_dev), _ptr(packed_sparse), fmt(fw),
+                                 _ptr(sw), _ptr(bias), _ptr(y), M, N, K, _ptr(workspace), wb, _stream()), "fpq_gemm_sparse")
+
+
+def fpq_conv2d_sparse(x, x_is_fp32, fx, sx, sx_dev, packed_sparse, fw, sw, bias, y, B, Cin, H, W, Cout, kh, kw, stride, pad,
+                      workspace=None):
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().fpq_conv2d_sparse(_ptr(x), int(x_is_fp32), fmt(fx), float(sx), _ptr(sx_dev), _ptr(packed_sparse), fmt(fw),
+                                   _ptr(sw), _ptr(bias), _ptr(y), B, Cin, H, W, Cout, kh, kw, stride, pad, _ptr(workspace), wb,
+                                   _stream()), "fpq_conv2d_sparse")
+
+
+FPQ_PROBE_MFMA_BF16, FPQ_PROBE_MFMA_FP8, FPQ_PROBE_COPY = 0, 1, 2
+
+
+def fpq_probe_peak(kind, iterations, src, dst):
+    """One probe launch; returns its work (flops, or bytes read + written)."""
+    work = C.c_double(0.0)
+    _check(lib().fpq_probe_peak(int(kind), int(iterations), _ptr(src), _ptr(dst), dst.numel() * dst.element_size(),
+                                C.byref(work), _stream()), "fpq_probe_peak")
+    return work.value
 
 
 def fpq_gemm_noalloc(x, x_is_fp32, fx, sx, sx_dev, packed_w, fw, sw, bias, y, M, N, K, acc_mode=FPQ_ACC_FP32):

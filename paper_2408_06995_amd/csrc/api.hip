@@ -467,10 +467,17 @@ struct CodesOut {
     uint8_t* yq;
 };
 
+// Geometry of the structured-sparse packed form: kept-code rows, then (256-byte aligned) the position words.
+static size_t sparse_code_row_bytes(int64_t kpad, fpq_format_t f) { return (size_t)(is_four_bit(f) ? kpad / 4 : kpad / 2); }
+static size_t sparse_pos_offset(int64_t N, int64_t kpad, fpq_format_t f)
+{
+    return kPackedRowsOffset + align_up((size_t)N * sparse_code_row_bytes(kpad, f), 256);
+}
+
 static int run_layer(const CodesOut* out, const void* x, int x_is_fp32, fpq_format_t fx, float sx, const float* sx_dev,
                      const void* packed_w, fpq_format_t fw, const float* sw, const float* bias, float* y, int64_t B,
                      int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh, int kw, int stride, int pad,
-                     int conv_out, int acc_mode, void* workspace, size_t workspace_bytes, void* stream)
+                     int conv_out, int acc_mode, void* workspace, size_t workspace_bytes, void* stream, bool sparse = false)
 {
     const int accumulate = (acc_mode & FPQ_OUT_ACCUMULATE) ? 1 : 0;
     const int act = acc_mode & (FPQ_ACT_SILU | FPQ_ACT_GEGLU);
@@ -516,6 +523,12 @@ static int run_layer(const CodesOut* out, const void* x, int x_is_fp32, fpq_form
     // workspace = [activation codes when the input is fp32][split-K partial results]; a caller that passes
     // codes and no (or too small a) workspace gets the unsplit kernel
     GemmPlan plan = plan_gemm(M, Cout, padded_k(Cin, (int64_t)kh * kw));
+    if (sparse) {
+        // the structured-sparse form has one kernel: hardware E4M3 activations, E4M3 / E2M1 weights, exact accumulate
+        if (out || accumulate || acc_mode != FPQ_ACC_FP32 || xkind != OPK_FP8 || (wkind != OPK_FP8 && wkind != OPK_FP4))
+            return FPQ_ERR_UNSUPPORTED;
+        plan = GemmPlan{TILE_GENERIC, 1};
+    }
     const size_t codes_bytes = x_is_fp32 ? align_up((size_t)B * H * W * (size_t)Cp, 256) : 0;
     const size_t part_bytes = align_up(split_workspace_bytes(plan, M, Cout), 256);
     if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255)) return FPQ_ERR_ALIGN;
@@ -568,7 +581,7 @@ static int run_layer(const CodesOut* out, const void* x, int x_is_fp32, fpq_form
         uint8_t* buf = static_cast<uint8_t*>(workspace);
         ScaleSrc ss{sx, sx_dev, nullptr, 0, 0.0f, nullptr};
         bool quantized = false;
-        if (dyn && !conv_out && Cp == Cin && M <= 16) {
+        if (dyn && !conv_out && Cp == Cin && M <= 16 && !sparse) {
             // at most 16 rows: maximum, scale, codes and the layer itself in one launch
             st = launch_gemm_skinny_dynamic(a, static_cast<const float*>(x), qx, qx.c, buf,
                                             reinterpret_cast<float*>(buf + codes_bytes + part_bytes) + 1024, s);
@@ -617,6 +630,9 @@ static int run_layer(const CodesOut* out, const void* x, int x_is_fp32, fpq_form
     }
     a.x = xcodes;
     a.sx_dev = sx_dev;
+    if (sparse)
+        return launch_gemm_sparse(a, reinterpret_cast<const uint32_t*>(static_cast<const uint8_t*>(packed_w) +
+                                                                       sparse_pos_offset(Cout, a.Kpad, fw)), s);
     if (!gemm_dma_applicable(a)) {   // operand pairing only the generic kernels serve
         a.tile = TILE_GENERIC;
         a.splits = 1;
@@ -765,6 +781,84 @@ int fpq_gemm_grouped(const fpq_gemm_problem_t* problems, int count, int x_is_fp3
         }
         if (st) return st;
     }
+    return FPQ_OK;
+}
+
+size_t fpq_packed_sparse_size(int64_t N, int64_t Cin, int kh, int kw, fpq_format_t f)
+{
+    if (N <= 0 || Cin <= 0 || kh <= 0 || kw <= 0 || resolve_format(f, nullptr)) return 0;
+    const int64_t kpad = padded_k(Cin, (int64_t)kh * kw);
+    return sparse_pos_offset(N, kpad, f) + (size_t)N * (size_t)(kpad / 8);
+}
+
+int fpq_pack_weights_sparse(const float* w, int64_t N, int64_t Cin, int kh, int kw, fpq_format_t f, const float* scale,
+                            const uint8_t* mask, void* packed, size_t packed_bytes, float* scale_out, uint8_t* codes_out,
+                            uint64_t* dropped_out, void* stream)
+{
+    QParams q;
+    int st = resolve_format(f, &q);
+    if (st) return st;
+    if (N <= 0 || Cin <= 0 || kh <= 0 || kw <= 0 || kh > 64 || kw > 64) return FPQ_ERR_SHAPE;
+    if (N > 0x7fffffff || Cin * kh * kw > (1 << 28)) return FPQ_ERR_SHAPE;
+    if (!w || !packed || !scale_out || !dropped_out) return FPQ_ERR_NULL;
+    if (packed_bytes < fpq_packed_sparse_size(N, Cin, kh, kw, f)) return FPQ_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(packed) & 255) || (reinterpret_cast<uintptr_t>(w) & 3) ||
+        (reinterpret_cast<uintptr_t>(dropped_out) & 7))
+        return FPQ_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    PackedHeader h;
+    memset(&h, 0, sizeof h);
+    h.magic = kPackedMagic;
+    h.layout = 2;
+    h.ebits = f.ebits; h.mbits = f.mbits; h.bias = f.bias;
+    h.maxval = q.c;
+    h.N = N; h.Cin = Cin; h.kh = kh; h.kw = kw;
+    h.Cp = (int32_t)padded_channels(Cin);
+    h.Kpad = (int32_t)padded_k(Cin, (int64_t)kh * kw);
+    hipLaunchKernelGGL(write_header_kernel, dim3(1), dim3(64), 0, s, h, static_cast<uint32_t*>(packed));
+    uint8_t* base = static_cast<uint8_t*>(packed);
+    return launch_pack_weights_sparse(w, N, Cin, kh * kw, q, is_four_bit(f), scale, mask, base + kPackedRowsOffset,
+                                      reinterpret_cast<uint32_t*>(base + sparse_pos_offset(N, h.Kpad, f)), scale_out, codes_out,
+                                      reinterpret_cast<unsigned long long*>(dropped_out), s);
+}
+
+int fpq_gemm_sparse(const void* x, int x_is_fp32, fpq_format_t fx, float sx, const float* sx_dev, const void* packed_sparse,
+                    fpq_format_t fw, const float* sw, const float* bias, float* y, int64_t M, int64_t N, int64_t K,
+                    void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (M == 0 && N > 0 && K > 0) return FPQ_OK;
+    if (packed_sparse && (reinterpret_cast<uintptr_t>(packed_sparse) & 255)) return FPQ_ERR_ALIGN;
+    return run_layer(nullptr, x, x_is_fp32, fx, sx, sx_dev, packed_sparse, fw, sw, bias, y, M, K, 1, 1, N, 1, 1, 1, 0, 0,
+                     FPQ_ACC_FP32, workspace, workspace_bytes, stream, true);
+}
+
+int fpq_conv2d_sparse(const void* x, int x_is_fp32, fpq_format_t fx, float sx, const float* sx_dev, const void* packed_sparse,
+                      fpq_format_t fw, const float* sw, const float* bias, float* y, int64_t B, int64_t Cin, int64_t H, int64_t W,
+                      int64_t Cout, int kh, int kw, int stride, int pad, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (packed_sparse && (reinterpret_cast<uintptr_t>(packed_sparse) & 255)) return FPQ_ERR_ALIGN;
+    return run_layer(nullptr, x, x_is_fp32, fx, sx, sx_dev, packed_sparse, fw, sw, bias, y, B, Cin, H, W, Cout, kh, kw, stride, pad,
+                     1, FPQ_ACC_FP32, workspace, workspace_bytes, stream, true);
+}
+
+int fpq_probe_peak(int kind, int iterations, const void* src, void* dst, size_t bytes, double* work_out, void* stream)
+{
+    if (kind < FPQ_PROBE_MFMA_BF16 || kind > FPQ_PROBE_COPY) return FPQ_ERR_UNSUPPORTED;
+    if (!dst || !work_out) return FPQ_ERR_NULL;
+    if (kind == FPQ_PROBE_COPY) {
+        if (!src) return FPQ_ERR_NULL;
+        if (bytes < 16 || ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15)) return FPQ_ERR_ALIGN;
+    } else {
+        if (iterations < 1 || iterations > (1 << 20)) return FPQ_ERR_SHAPE;
+        if (bytes < (size_t)2048 * 256 * sizeof(float)) return FPQ_ERR_WORKSPACE;
+    }
+    int grid = 0;
+    const int st = launch_probe(kind, iterations, src, dst, bytes, &grid, static_cast<hipStream_t>(stream));
+    if (st) return st;
+    if (kind == FPQ_PROBE_COPY)
+        *work_out = 2.0 * (double)(bytes / 16 * 16);                                  // bytes read + written
+    else                                                                              // flops: 32 MFMAs per iteration and wave
+        *work_out = (double)grid * 4.0 * iterations * 32.0 * 2.0 * 32 * 32 * (kind == FPQ_PROBE_MFMA_BF16 ? 16 : 64);
     return FPQ_OK;
 }
 

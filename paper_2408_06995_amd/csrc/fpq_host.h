@@ -247,6 +247,13 @@ int launch_gemm_grouped(const GroupedArgs& g, hipStream_t st);                 /
 bool skinny_grouped_applicable(const GroupedArgs& g);                           // all problems: at most 16 rows, <= 16 Ki activations
 int launch_gemm_skinny_dynamic_grouped(const GroupedArgs& g, const QParams& qx, float maxval, hipStream_t st);
 int launch_quantize_dynamic_grouped(const GroupedArgs& g, const QParams& qx, float maxval, hipStream_t st);
+// Structured-sparse weight operand (gemm_sparse.hip).
+int launch_pack_weights_sparse(const float* w, int64_t N, int64_t Cin, int taps, const QParams& q, bool four_bit,
+                               const float* scale_in, const uint8_t* mask, uint8_t* code_rows, uint32_t* pos_rows,
+                               float* scale_out, uint8_t* codes_out, unsigned long long* altered, hipStream_t st);
+int launch_gemm_sparse(const GemmArgs& a, const uint32_t* pos_rows, hipStream_t st);
+// Machine-ceiling probes (peaks.hip): kind 0 / 1 = register-only bf16 / 8-bit MFMA loop, 2 = device copy.
+int launch_probe(int kind, int iters, const void* src, void* dst, size_t bytes, int* grid_out, hipStream_t st);
 bool gemm_dma_applicable(const GemmArgs& a);
 int launch_gemm_dma(const GemmArgs& a, hipStream_t st);
 int launch_gemm_dma_q(const GemmArgs& a, hipStream_t st);   // the same with the result as codes (a.yq)
