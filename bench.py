@@ -540,6 +540,74 @@ def main():
                       "the nominal peaks are %g / %g TFLOP/s and %g GB/s" % (PEAK_BF16_TFLOPS, PEAK_FP8_TFLOPS, PEAK_HBM_GBS))
         roofline["measured_peak"] = pk
         roofline["frac_of_measured_peak"] = round(achieved / pk["bf16_mfma_TFLOP/s" if acc == B.FPQ_ACC_FP32 else "fp8_mfma_TFLOP/s"], 4)
+        # structured-sparse weight operand (2 of every 4 input channels kept): the configuration-4 convolution and a
+        # 1280-wide linear layer, E2M1 weights, layer kernel alone on prepared codes, next to the dense call on the same
+        # shape; TFLOP/s count the dense layer's 2MNK
+        sp = {}
+        for cname, L in (("cfg4_conv_1280_16x16_b8", synth.config_layers(4)[0]), ("linear_2048x1280x1280", synth.linear("l", 2048, 1280, 1280))):
+            if L.kind == "conv":
+                xs = synth.activations_torch((L.B, L.Cin, L.H, L.W), 1, dev)
+                wshape, kk = (L.Cout, L.Cin, L.k, L.k), L.k
+                cb = torch.empty(L.B * L.H * L.W * B.fpq_padded_channels(L.Cin), dtype=torch.uint8, device=dev)
+                wsz = B.fpq_conv2d_workspace_size(L.B, L.Cin, L.H, L.W, L.Cout, L.k, L.k, L.stride, L.pad, 0)
+            else:
+                xs = synth.activations_torch((L.M, L.K), 1, dev)
+                wshape, kk = (L.N, L.K), 1
+                cb = torch.empty(L.M * L.K, dtype=torch.uint8, device=dev)
+                wsz = B.fpq_gemm_workspace_size(L.M, L.N, L.K, 0)
+            w = synth.weights_torch(wshape, 2, dev)
+            st2 = torch.empty(2, dtype=torch.float32, device=dev)
+            B.fpq_absmax(xs, FX[3], st2[0:1], st2[1:2], amax_ws)
+            if L.kind == "conv":
+                B.fpq_quantize_nhwc(xs, FX, 0.0, st2[1:2], cb)
+            else:
+                B.fpq_quantize(xs, FX, 0.0, st2[1:2], cb)
+            yb = torch.empty(L.M * L.N, dtype=torch.float32, device=dev)
+            wsb = torch.empty(max(256, wsz), dtype=torch.uint8, device=dev)
+            pk = torch.empty(B.fpq_packed_size(L.N, L.Cin, kk, kk, FW4), dtype=torch.uint8, device=dev)
+            pks = torch.empty(B.fpq_packed_sparse_size(L.N, L.Cin, kk, kk, FW4), dtype=torch.uint8, device=dev)
+            sw = torch.empty(L.N, dtype=torch.float32, device=dev)
+            dropped = torch.zeros(1, dtype=torch.int64, device=dev)
+            B.fpq_pack_weights(w, FW4, None, None, pk, sw, None)
+            B.fpq_pack_weights_sparse(w, FW4, None, None, pks, sw, None, dropped)
+
+            def dense():
+                if L.kind == "conv":
+                    B.fpq_conv2d(cb, 0, FX, 0.0, st2[1:2], pk, FW4, sw, None, yb, L.B, L.Cin, L.H, L.W, L.Cout, L.k, L.k,
+                                 L.stride, L.pad, B.FPQ_ACC_FP32, wsb)
+                else:
+                    B.fpq_gemm(cb, 0, FX, 0.0, st2[1:2], pk, FW4, sw, None, yb, L.M, L.N, L.K, B.FPQ_ACC_FP32, wsb)
+
+            def sparse():
+                if L.kind == "conv":
+                    B.fpq_conv2d_sparse(cb, 0, FX, 0.0, st2[1:2], pks, FW4, sw, None, yb, L.B, L.Cin, L.H, L.W, L.Cout, L.k, L.k,
+                                        L.stride, L.pad, wsb)
+                else:
+                    B.fpq_gemm_sparse(cb, 0, FX, 0.0, st2[1:2], pks, FW4, sw, None, yb, L.M, L.N, L.K, wsb)
+            ent = {}
+            for name, fn in (("dense", dense), ("sparse", sparse)):
+                fn()
+                torch.cuda.synchronize()
+                gs = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gs):
+                    for _ in range(16):
+                        fn()
+                gs.replay()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(4):
+                    gs.replay()
+                e1.record()
+                e1.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / 64
+                ent[name] = {"us": round(us, 2), "TFLOP/s_of_2MNK": round(synth.flops(L) / us / 1e6, 1)}
+            groups4 = L.N * kk * kk * ((L.Cin + 3) // 4)
+            ent["weight_bytes_dense"] = pk.numel()
+            ent["weight_bytes_sparse"] = pks.numel()
+            ent["groups_that_lost_a_nonzero"] = round(int(dropped.item()) / groups4, 4)
+            sp[cname] = ent
+            del xs, w, cb, yb, wsb, pk, pks
+        out["sparse_weights_e2m1"] = sp
         # encoding / bias search of Section V-A on one activation tensor (8 x 320 x 64 x 64): 4 FP8 encodings x 111
         # bias candidates; bound by vector ALU work: 11 vector instructions per element and candidate (SEARCH_OPS) against the lane-instruction rate of the chip
         xs = synth.activations_torch((8, 320, 64, 64), 3, dev).reshape(-1)

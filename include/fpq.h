@@ -361,6 +361,43 @@ int fpq_conv2d_sparse(const void *x, int x_is_fp32, fpq_format_t fx, float sx, c
                       int64_t B, int64_t Cin, int64_t H, int64_t W, int64_t Cout, int kh, int kw, int stride,
                       int pad, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- the same-bitwidth integer baseline (Section IV-A, Eq. (4)) ------------------------------------
+ *
+ * The uniform integer quantizer the paper measures its floating-point formats against,
+ *     X_int = s (clamp(round(X / s) + z; 0, 2^b - 1) - z),   s = (max X - min X) / (2^b - 1),   z = -round(min X / s),
+ * and a linear layer on its codes, Y[m, n] = sx sw[n] sum_k (qx[m, k] - zx)(qw[n, k] - zw[n]) (+ bias[n]), computed
+ * with the 8-bit integer matrix instruction: the sum is exact (32-bit integers), the scaling is one fp32 multiply.
+ * bits is 8 or 4 (FPQ_ERR_FORMAT otherwise).  Codes are one per byte (0 .. 2^b - 1) in all caller-visible buffers.
+ * Rounding is to nearest, ties to the even integer; in fp32: s = fl32(fl32(max - min) / (2^b - 1)) (1 for a constant
+ * tensor), every quotient is fl32(x * fl32(1 / s)), z is not clamped to the code range.  NaN inputs give code 0.
+ *
+ * fpq_int_calibrate: min, max, s and z of x[n] into *params_out (device memory); workspace
+ *   fpq_int_calibrate_workspace_size bytes.
+ * fpq_int_quantize: codes of x with (scale, zero_point), or with *params_dev when that is not NULL.
+ * fpq_int_pack_weights: w[N, K] fp32 -> per-output-channel (s, z) by the same equation, codes in the layout the layer
+ *   kernel streams (fpq_int_packed_size bytes, 256-byte aligned) with each row's code sum; scale_out[N],
+ *   zero_point_out[N]; codes_out (or NULL) the plain codes [N, K].  K <= 32768.
+ * fpq_int_gemm: xcodes [M, K] 8-bit activation codes (K % 16 == 0, 16-byte aligned) with (sx, zx) or *px_dev;
+ *   packed_w / wbits / sw / zw from fpq_int_pack_weights; y[M, N] fp32; workspace fpq_int_gemm_workspace_size(M)
+ *   bytes (the row sums of the activation codes). */
+typedef struct fpq_int_params {
+    float scale;
+    int32_t zero_point;
+    float min, max;
+} fpq_int_params;
+size_t fpq_int_calibrate_workspace_size(size_t n);
+int fpq_int_calibrate(const float *x, size_t n, int bits, fpq_int_params *params_out, void *workspace,
+                      size_t workspace_bytes, void *stream);
+int fpq_int_quantize(const float *x, size_t n, int bits, float scale, int32_t zero_point,
+                     const fpq_int_params *params_dev, uint8_t *codes, void *stream);
+size_t fpq_int_packed_size(int64_t N, int64_t K, int bits);
+int fpq_int_pack_weights(const float *w, int64_t N, int64_t K, int bits, void *packed, size_t packed_bytes,
+                         float *scale_out, int32_t *zero_point_out, uint8_t *codes_out, void *stream);
+size_t fpq_int_gemm_workspace_size(int64_t M);
+int fpq_int_gemm(const uint8_t *xcodes, float sx, int32_t zx, const fpq_int_params *px_dev, const void *packed_w,
+                 int wbits, const float *sw, const int32_t *zw, const float *bias, float *y, int64_t M, int64_t N,
+                 int64_t K, void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- a group of independent linear layers in one call -----------------------------------------
  *
  * Several linear layers that do not depend on each other (in the U-Net: the key / value projections of all

@@ -134,6 +134,20 @@ def lib():
     L.fpq_gemm_sparse.argtypes = [vp, i32, F, fl, f32p, vp, F, f32p, f32p, f32p, i64, i64, i64, vp, sz, vp]
     L.fpq_conv2d_sparse.restype = i32
     L.fpq_conv2d_sparse.argtypes = ([vp, i32, F, fl, f32p, vp, F, f32p, f32p, f32p] + [i64] * 5 + [i32] * 4 + [vp, sz, vp])
+    L.fpq_int_calibrate_workspace_size.restype = sz
+    L.fpq_int_calibrate_workspace_size.argtypes = [sz]
+    L.fpq_int_calibrate.restype = i32
+    L.fpq_int_calibrate.argtypes = [f32p, sz, i32, vp, vp, sz, vp]
+    L.fpq_int_quantize.restype = i32
+    L.fpq_int_quantize.argtypes = [f32p, sz, i32, fl, C.c_int32, vp, u8p, vp]
+    L.fpq_int_packed_size.restype = sz
+    L.fpq_int_packed_size.argtypes = [i64, i64, i32]
+    L.fpq_int_pack_weights.restype = i32
+    L.fpq_int_pack_weights.argtypes = [f32p, i64, i64, i32, vp, sz, f32p, vp, u8p, vp]
+    L.fpq_int_gemm_workspace_size.restype = sz
+    L.fpq_int_gemm_workspace_size.argtypes = [i64]
+    L.fpq_int_gemm.restype = i32
+    L.fpq_int_gemm.argtypes = [u8p, fl, C.c_int32, vp, vp, i32, f32p, vp, f32p, f32p, i64, i64, i64, vp, sz, vp]
     L.fpq_probe_peak.restype = i32
     L.fpq_probe_peak.argtypes = [i32, i32, vp, vp, sz, C.POINTER(C.c_double), vp]
     L.fpq_gemm_noalloc.restype = i32
@@ -149,7 +163,9 @@ EXPORTS = ["fpq_strerror", "fpq_format_max", "fpq_format_check", "fpq_bias_to_sc
            "fpq_count_zeros_workspace_size", "fpq_count_zeros", "fpq_gemm_codes_out", "fpq_conv2d_codes_out",
            "fpq_rl_workspace_size", "fpq_rl_init_alpha", "fpq_rl_step", "fpq_rl_mask", "fpq_packed_check", "fpq_rl_im2col",
            "fpq_gemm_plan", "fpq_conv2d_plan", "fpq_gemm_noalloc", "fpq_gemm_grouped_workspace_size", "fpq_gemm_grouped", "fpq_probe_peak",
-           "fpq_packed_sparse_size", "fpq_pack_weights_sparse", "fpq_gemm_sparse", "fpq_conv2d_sparse"]
+           "fpq_packed_sparse_size", "fpq_pack_weights_sparse", "fpq_gemm_sparse", "fpq_conv2d_sparse",
+           "fpq_int_calibrate_workspace_size", "fpq_int_calibrate", "fpq_int_quantize", "fpq_int_packed_size",
+           "fpq_int_pack_weights", "fpq_int_gemm_workspace_size", "fpq_int_gemm"]
 
 
 def fmt(f):
@@ -345,6 +361,45 @@ def fpq_conv2d_sparse(x, x_is_fp32, fx, sx, sx_dev, packed_sparse, fw, sw, bias,
     _check(lib().fpq_conv2d_sparse(_ptr(x), int(x_is_fp32), fmt(fx), float(sx), _ptr(sx_dev), _ptr(packed_sparse), fmt(fw),
                                    _ptr(sw), _ptr(bias), _ptr(y), B, Cin, H, W, Cout, kh, kw, stride, pad, _ptr(workspace), wb,
                                    _stream()), "fpq_conv2d_sparse")
+
+
+class fpq_int_params(C.Structure):
+    _fields_ = [("scale", C.c_float), ("zero_point", C.c_int32), ("min", C.c_float), ("max", C.c_float)]
+
+
+def fpq_int_calibrate(x, bits, params_out, workspace):
+    """params_out: uint8 tensor of 16 bytes (read it back with int_params())."""
+    _check(lib().fpq_int_calibrate(_ptr(x), x.numel(), int(bits), _ptr(params_out), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream()), "fpq_int_calibrate")
+
+
+def int_params(params):
+    return fpq_int_params.from_buffer_copy(bytes(params.cpu().numpy().tobytes()[:C.sizeof(fpq_int_params)]))
+
+
+def fpq_int_quantize(x, bits, scale, zero_point, params_dev, codes):
+    _check(lib().fpq_int_quantize(_ptr(x), x.numel(), int(bits), float(scale), int(zero_point), _ptr(params_dev), _ptr(codes),
+                                  _stream()), "fpq_int_quantize")
+
+
+def fpq_int_packed_size(N, K, bits):
+    return lib().fpq_int_packed_size(N, K, int(bits))
+
+
+def fpq_int_pack_weights(w, bits, packed, scale_out, zero_point_out, codes_out=None):
+    N, K = w.shape
+    _check(lib().fpq_int_pack_weights(_ptr(w), N, K, int(bits), _ptr(packed), packed.numel() * packed.element_size(),
+                                      _ptr(scale_out), _ptr(zero_point_out), _ptr(codes_out), _stream()), "fpq_int_pack_weights")
+
+
+def fpq_int_gemm_workspace_size(M):
+    return lib().fpq_int_gemm_workspace_size(M)
+
+
+def fpq_int_gemm(xcodes, sx, zx, px_dev, packed_w, wbits, sw, zw, bias, y, M, N, K, workspace):
+    _check(lib().fpq_int_gemm(_ptr(xcodes), float(sx), int(zx), _ptr(px_dev), _ptr(packed_w), int(wbits), _ptr(sw), _ptr(zw),
+                              _ptr(bias), _ptr(y), M, N, K, _ptr(workspace), workspace.numel() * workspace.element_size(),
+                              _stream()), "fpq_int_gemm")
 
 
 FPQ_PROBE_MFMA_BF16, FPQ_PROBE_MFMA_FP8, FPQ_PROBE_COPY = 0, 1, 2

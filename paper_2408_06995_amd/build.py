@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libfpq.so")
 OBJ = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "quant.hip", "search.hip", "sparsity.hip", "rounding.hip", "gemm.hip", "gemm_dma.hip", "gemm_dma_q.hip", "peaks.hip", "gemm_sparse.hip"]
+SOURCES = ["api.hip", "quant.hip", "search.hip", "sparsity.hip", "rounding.hip", "gemm.hip", "gemm_dma.hip", "gemm_dma_q.hip", "peaks.hip", "gemm_sparse.hip", "igemm.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

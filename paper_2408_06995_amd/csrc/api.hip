@@ -841,6 +841,94 @@ int fpq_conv2d_sparse(const void* x, int x_is_fp32, fpq_format_t fx, float sx, c
                      1, FPQ_ACC_FP32, workspace, workspace_bytes, stream, true);
 }
 
+// ---- uniform integer baseline (Section IV-A, Eq. (4))
+
+static bool int_bits_ok(int bits) { return bits == 8 || bits == 4; }
+static size_t int_rows_bytes(int64_t N, int64_t K, int bits)
+{
+    const size_t kpad = (size_t)padded_k(K, 1);
+    return (size_t)N * (bits == 4 ? kpad / 2 : kpad);
+}
+
+size_t fpq_int_calibrate_workspace_size(size_t) { return 2 * 1024 * sizeof(float); }
+
+int fpq_int_calibrate(const float* x, size_t n, int bits, fpq_int_params* params_out, void* workspace, size_t workspace_bytes,
+                      void* stream)
+{
+    if (!int_bits_ok(bits)) return FPQ_ERR_FORMAT;
+    if (!params_out || !workspace || (n && !x)) return FPQ_ERR_NULL;
+    if (workspace_bytes < fpq_int_calibrate_workspace_size(n)) return FPQ_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(x) & 3) || (reinterpret_cast<uintptr_t>(workspace) & 3) ||
+        (reinterpret_cast<uintptr_t>(params_out) & 3))
+        return FPQ_ERR_ALIGN;
+    return launch_int_params(x, n, bits, params_out, static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+int fpq_int_quantize(const float* x, size_t n, int bits, float scale, int32_t zero_point, const fpq_int_params* params_dev,
+                     uint8_t* codes, void* stream)
+{
+    if (!int_bits_ok(bits)) return FPQ_ERR_FORMAT;
+    if (!params_dev && !scale_ok(scale)) return FPQ_ERR_SCALE;
+    if (!params_dev && (zero_point < -(1 << 24) || zero_point > (1 << 24))) return FPQ_ERR_SCALE;
+    if (n == 0) return FPQ_OK;
+    if (!x || !codes) return FPQ_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(x) & 3) return FPQ_ERR_ALIGN;
+    return launch_int_quantize(x, n, bits, scale, zero_point, params_dev, codes, static_cast<hipStream_t>(stream));
+}
+
+size_t fpq_int_packed_size(int64_t N, int64_t K, int bits)
+{
+    if (N <= 0 || K <= 0 || !int_bits_ok(bits)) return 0;
+    return kPackedRowsOffset + align_up(int_rows_bytes(N, K, bits), 256) + (size_t)N * sizeof(int32_t);
+}
+
+int fpq_int_pack_weights(const float* w, int64_t N, int64_t K, int bits, void* packed, size_t packed_bytes, float* scale_out,
+                         int32_t* zero_point_out, uint8_t* codes_out, void* stream)
+{
+    if (!int_bits_ok(bits)) return FPQ_ERR_FORMAT;
+    if (N <= 0 || K <= 0 || N > 0x7fffffff || K > 32768) return FPQ_ERR_SHAPE;
+    if (!w || !packed || !scale_out || !zero_point_out) return FPQ_ERR_NULL;
+    if (packed_bytes < fpq_int_packed_size(N, K, bits)) return FPQ_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(packed) & 255) || (reinterpret_cast<uintptr_t>(w) & 3)) return FPQ_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    PackedHeader h;
+    memset(&h, 0, sizeof h);
+    h.magic = kPackedMagic;
+    h.layout = 3;                 // integer codes
+    h.mbits = bits;
+    h.N = N; h.Cin = K; h.kh = h.kw = 1;
+    h.Cp = (int32_t)padded_channels(K);
+    h.Kpad = (int32_t)padded_k(K, 1);
+    hipLaunchKernelGGL(write_header_kernel, dim3(1), dim3(64), 0, s, h, static_cast<uint32_t*>(packed));
+    uint8_t* base = static_cast<uint8_t*>(packed);
+    int32_t* rowsum = reinterpret_cast<int32_t*>(base + kPackedRowsOffset + align_up(int_rows_bytes(N, K, bits), 256));
+    return launch_int_pack_weights(w, N, K, bits, base + kPackedRowsOffset, scale_out, zero_point_out, rowsum, codes_out, s);
+}
+
+size_t fpq_int_gemm_workspace_size(int64_t M) { return M > 0 ? align_up((size_t)M * sizeof(int32_t), 256) : 0; }
+
+int fpq_int_gemm(const uint8_t* xcodes, float sx, int32_t zx, const fpq_int_params* px_dev, const void* packed_w, int wbits,
+                 const float* sw, const int32_t* zw, const float* bias, float* y, int64_t M, int64_t N, int64_t K,
+                 void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!int_bits_ok(wbits)) return FPQ_ERR_FORMAT;
+    if (M == 0 && N > 0 && K > 0) return FPQ_OK;
+    if (M <= 0 || N <= 0 || K <= 0 || M >= (int64_t)1 << 31 || N >= (int64_t)1 << 24 || K > 32768 || M * N >= (int64_t)1 << 40 ||
+        M * K >= (int64_t)1 << 40)
+        return FPQ_ERR_SHAPE;
+    if (!px_dev && !scale_ok(sx)) return FPQ_ERR_SCALE;
+    if (!px_dev && (zx < -(1 << 24) || zx > (1 << 24))) return FPQ_ERR_SCALE;
+    if (!xcodes || !packed_w || !sw || !zw || !y || !workspace) return FPQ_ERR_NULL;
+    if ((K & 15) || (reinterpret_cast<uintptr_t>(xcodes) & 15) || (reinterpret_cast<uintptr_t>(packed_w) & 255) ||
+        (reinterpret_cast<uintptr_t>(y) & 3) || (reinterpret_cast<uintptr_t>(workspace) & 3))
+        return FPQ_ERR_ALIGN;
+    if (workspace_bytes < fpq_int_gemm_workspace_size(M)) return FPQ_ERR_WORKSPACE;
+    const uint8_t* base = static_cast<const uint8_t*>(packed_w);
+    const int32_t* rowsum = reinterpret_cast<const int32_t*>(base + kPackedRowsOffset + align_up(int_rows_bytes(N, K, wbits), 256));
+    return launch_int_gemm(xcodes, sx, zx, px_dev, base + kPackedRowsOffset, rowsum, wbits, sw, zw, bias, y, M, N, K,
+                           static_cast<int32_t*>(workspace), static_cast<hipStream_t>(stream));
+}
+
 int fpq_probe_peak(int kind, int iterations, const void* src, void* dst, size_t bytes, double* work_out, void* stream)
 {
     if (kind < FPQ_PROBE_MFMA_BF16 || kind > FPQ_PROBE_COPY) return FPQ_ERR_UNSUPPORTED;

@@ -252,6 +252,15 @@ int launch_pack_weights_sparse(const float* w, int64_t N, int64_t Cin, int taps,
                                const float* scale_in, const uint8_t* mask, uint8_t* code_rows, uint32_t* pos_rows,
                                float* scale_out, uint8_t* codes_out, unsigned long long* altered, hipStream_t st);
 int launch_gemm_sparse(const GemmArgs& a, const uint32_t* pos_rows, hipStream_t st);
+// Uniform integer baseline of Eq. (4) (igemm.hip).
+int launch_int_params(const float* x, size_t n, int bits, fpq_int_params* out, float* partial, hipStream_t st);
+int launch_int_quantize(const float* x, size_t n, int bits, float scale, int zp, const fpq_int_params* params_dev, uint8_t* codes,
+                        hipStream_t st);
+int launch_int_pack_weights(const float* w, int64_t N, int64_t K, int bits, uint8_t* rows, float* scale_out, int32_t* zp_out,
+                            int32_t* rowsum_out, uint8_t* codes_out, hipStream_t st);
+int launch_int_gemm(const uint8_t* x, float sx, int zx, const fpq_int_params* px_dev, const uint8_t* wrows, const int32_t* wsum,
+                    int wbits, const float* sw, const int32_t* zw, const float* bias, float* y, int64_t M, int64_t N, int64_t K,
+                    int32_t* xsum, hipStream_t st);
 // Machine-ceiling probes (peaks.hip): kind 0 / 1 = register-only bf16 / 8-bit MFMA loop, 2 = device copy.
 int launch_probe(int kind, int iters, const void* src, void* dst, size_t bytes, int* grid_out, hipStream_t st);
 bool gemm_dma_applicable(const GemmArgs& a);
