@@ -608,6 +608,47 @@ def main():
             sp[cname] = ent
             del xs, w, cb, yb, wsb, pk, pks
         out["sparse_weights_e2m1"] = sp
+        # the same-bitwidth integer baseline of Eq. (4) on two linear layers of the set (integer matrix instruction, exact
+        # sums; peak 5.0 POP/s), next to the floating-point layer on the same shapes: layer kernel alone on prepared codes
+        ib = {}
+        for cname, (iM, iK, iN) in (("linear_2048x1280x10240", (2048, 1280, 10240)), ("linear_32768x320x2560", (32768, 320, 2560))):
+            xs = synth.activations_torch((iM, iK), 1, dev)
+            w = synth.weights_torch((iN, iK), 2, dev)
+            ipar = torch.zeros(16, dtype=torch.uint8, device=dev)
+            iws = torch.empty(8192, dtype=torch.uint8, device=dev)
+            B.fpq_int_calibrate(xs, 8, ipar, iws)
+            xc = torch.empty(iM * iK, dtype=torch.uint8, device=dev)
+            B.fpq_int_quantize(xs, 8, 0.0, 0, ipar, xc)
+            yb = torch.empty(iM * iN, dtype=torch.float32, device=dev)
+            gws = torch.empty(max(256, B.fpq_int_gemm_workspace_size(iM)), dtype=torch.uint8, device=dev)
+            ent = {}
+            for wbits in (8, 4):
+                ipk = torch.empty(B.fpq_int_packed_size(iN, iK, wbits), dtype=torch.uint8, device=dev)
+                isw = torch.empty(iN, dtype=torch.float32, device=dev)
+                izw = torch.empty(iN, dtype=torch.int32, device=dev)
+                B.fpq_int_pack_weights(w, wbits, ipk, isw, izw, None)
+
+                def ione():
+                    B.fpq_int_gemm(xc, 0.0, 0, ipar, ipk, wbits, isw, izw, None, yb, iM, iN, iK, gws)
+                ione()
+                torch.cuda.synchronize()
+                gi = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gi):
+                    for _ in range(16):
+                        ione()
+                gi.replay()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(4):
+                    gi.replay()
+                e1.record()
+                e1.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / 64
+                tops = 2.0 * iM * iN * iK / us / 1e6
+                ent["w%da8" % wbits] = {"us": round(us, 2), "TOP/s": round(tops, 1), "frac_of_int8_peak": round(tops / 5000.0, 4)}
+            ib[cname] = ent
+            del xs, w, xc, yb
+        out["integer_baseline"] = ib
         # encoding / bias search of Section V-A on one activation tensor (8 x 320 x 64 x 64): 4 FP8 encodings x 111
         # bias candidates; bound by vector ALU work: 11 vector instructions per element and candidate (SEARCH_OPS) against the lane-instruction rate of the chip
         xs = synth.activations_torch((8, 320, 64, 64), 3, dev).reshape(-1)
