@@ -33,7 +33,11 @@ SEARCH_OPS = 11                        # vector instructions per element and can
 # HBM-side bytes per layer launch from two hardware-counter passes of a profiler (FETCH_SIZE, then WRITE_SIZE, the
 # split-K reductions included): not measurable from inside this script, hence a constant, valid only for the workload,
 # accumulate mode and call structure it was taken on; the summary file named here holds the command and the arithmetic.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    ("cfg5", "fp32", "grouped"): {"bytes_per_launch": 65.18e6,
+                                  "source": "profiles/cfg5_layer_kernels_hbm_traffic_pmc.txt: 30.53 MB fetched + 34.65 MB written "
+                                            "per layer over 4 x 500 layers"},
+}
 
 
 def parse():
@@ -325,7 +329,7 @@ def main():
                 "frac_of_fp8_peak": round(achieved / PEAK_FP8_TFLOPS, 4),
                 "traffic": None if traffic is None else traffic["bytes_per_launch"],
                 "traffic_source": None if traffic is None else traffic["source"],
-                "traffic_unit": "bytes per launch (L2 <-> fabric, rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, "
+                "traffic_unit": "bytes per layer launch (L2 <-> fabric, rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, "
                                 "factors from a 256 MiB copy kernel)",
                 "algorithmic_bytes_per_launch": round(alg_bytes / g_n),
                 "launches": g_n, "avg_launch_us": round(g_ms * 1e3 / g_n, 2),
@@ -344,6 +348,32 @@ def main():
         "roofline": roofline,
     }
 
+    def measure_peaks():
+        """What the part sustains on the bare matrix instructions and on a plain copy (probe kernels of the library)."""
+        pk = {}
+        pdst = torch.empty(2048 * 256, dtype=torch.float32, device=dev)
+        for name, kind, iters in (("bf16_mfma_TFLOP/s", B.FPQ_PROBE_MFMA_BF16, 1500), ("fp8_mfma_TFLOP/s", B.FPQ_PROBE_MFMA_FP8, 1500)):
+            B.fpq_probe_peak(kind, 100, None, pdst)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            work = sum(B.fpq_probe_peak(kind, iters, None, pdst) for _ in range(3))
+            e1.record()
+            e1.synchronize()
+            pk[name] = round(work / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+        csrc = [torch.empty(128 << 20, dtype=torch.float32, device=dev).normal_() for _ in range(2)]   # 512 MiB each
+        cdst = [torch.empty(128 << 20, dtype=torch.float32, device=dev) for _ in range(2)]
+        B.fpq_probe_peak(B.FPQ_PROBE_COPY, 1, csrc[0], cdst[0])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        work = sum(B.fpq_probe_peak(B.FPQ_PROBE_COPY, 1, csrc[i & 1], cdst[i & 1]) for i in range(8))
+        e1.record()
+        e1.synchronize()
+        pk["copy_GB/s_read_plus_write"] = round(work / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+        del csrc, cdst
+        pk["note"] = ("register-only MFMA loops with operands that change every instruction, and a 512 MiB device copy; "
+                      "the nominal peaks are %g / %g TFLOP/s and %g GB/s" % (PEAK_BF16_TFLOPS, PEAK_FP8_TFLOPS, PEAK_HBM_GBS))
+        return pk
+
     if args.per_class:
         # one representative layer per distinct (kind, kernel, stride, M, K, N); 8 launches in a graph, 4 replays
         seen, lines = {}, []
@@ -352,11 +382,16 @@ def main():
             key = (L.kind, L.k if L.kind == "conv" else 1, L.stride if L.kind == "conv" else 1, L.M, L.K, L.N)
             seen.setdefault(key, [s, 0])[1] += 1
         peak_fl = (PEAK_BF16_TFLOPS if acc == B.FPQ_ACC_FP32 else PEAK_FP8_TFLOPS) * 1e12
+        mp = measure_peaks()
+        m_fl = mp["bf16_mfma_TFLOP/s" if acc == B.FPQ_ACC_FP32 else "fp8_mfma_TFLOP/s"] * 1e12
+        m_bw = mp["copy_GB/s_read_plus_write"] * 1e9
         lines.append("# per shape class of %s, accumulate mode %s: layer kernel alone on prepared codes" % (args.workload, args.acc))
-        lines.append("# t_min = max(2MNK / %.0f TFLOP/s, (activation codes + packed weights + fp32 output) / 8 TB/s)" % (peak_fl / 1e12))
-        lines.append("%-4s %-6s %1s %1s %6s %6s %6s %4s %9s %9s %7s %9s %6s" % (
-            "w", "kind", "k", "s", "M", "K", "N", "x", "us", "TFLOP/s", "%peak", "%roofline", "bound"))
-        tot_t, tot_min = 0.0, 0.0
+        lines.append("# t_min = max(2MNK / %.0f TFLOP/s, (activation codes + packed weights + fp32 output) / 8 TB/s): the published peaks" % (peak_fl / 1e12))
+        lines.append("# %%machine = the same with what this part sustained in this run on the bare matrix instruction (%.0f TFLOP/s) and "
+                     "on a device copy (%.0f GB/s read + write)" % (m_fl / 1e12, m_bw / 1e9))
+        lines.append("%-4s %-6s %1s %1s %6s %6s %6s %4s %9s %9s %7s %9s %6s %9s" % (
+            "w", "kind", "k", "s", "M", "K", "N", "x", "us", "TFLOP/s", "%peak", "%roofline", "bound", "%machine"))
+        tot_t, tot_min, tot_mach = 0.0, 0.0, 0.0
         for key, (s, cnt) in seen.items():
             L = s.L
             buf = codes_bufs.get(L.name)
@@ -388,13 +423,16 @@ def main():
                 nbytes = buf.numel() + s.packed[tag].numel() + 4 * L.M * L.N
                 t_f, t_b = fl / peak_fl * 1e6, nbytes / (PEAK_HBM_GBS * 1e9) * 1e6
                 t_min = max(t_f, t_b)
-                lines.append("%-4s %-6s %1d %1d %6d %6d %6d %4d %9.1f %9.1f %7.1f %9.1f %6s" % (
+                t_mach = max(fl / m_fl * 1e6, nbytes / m_bw * 1e6)
+                lines.append("%-4s %-6s %1d %1d %6d %6d %6d %4d %9.1f %9.1f %7.1f %9.1f %6s %9.1f" % (
                     tag, L.kind, key[1], key[2], L.M, L.K, L.N, cnt, us, fl / us / 1e6, 100 * fl / (us * 1e-6) / peak_fl,
-                    100 * t_min / us, "mfma" if t_f >= t_b else "hbm"))
+                    100 * t_min / us, "mfma" if t_f >= t_b else "hbm", 100 * t_mach / us))
                 tot_t += us * cnt
                 tot_min += t_min * cnt
-        lines.append("# all layers of the step, each class weighted by its count: %.1f us against a roofline t_min of %.1f us (%.1f %%)"
-                     % (tot_t, tot_min, 100 * tot_min / tot_t))
+                tot_mach += t_mach * cnt
+        lines.append("# all layers of the step, each class weighted by its count: %.1f us against a roofline t_min of %.1f us (%.1f %%); "
+                     "against the machine's measured ceilings %.1f us (%.1f %%)"
+                     % (tot_t, tot_min, 100 * tot_min / tot_t, tot_mach, 100 * tot_mach / tot_t))
         with open(args.per_class, "w") as f:
             f.write("\n".join(lines) + "\n")
 
@@ -515,31 +553,9 @@ def main():
             singles[cname] = entry
             del xs, w, cb, yb, yq, wsb
         out["single_layers"] = singles
-        # what the part sustains on the bare matrix instructions and on a plain copy (probe kernels of the library)
-        pk = {}
-        pdst = torch.empty(2048 * 256, dtype=torch.float32, device=dev)
-        for name, kind, iters in (("bf16_mfma_TFLOP/s", B.FPQ_PROBE_MFMA_BF16, 1500), ("fp8_mfma_TFLOP/s", B.FPQ_PROBE_MFMA_FP8, 1500)):
-            B.fpq_probe_peak(kind, 100, None, pdst)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            work = sum(B.fpq_probe_peak(kind, iters, None, pdst) for _ in range(3))
-            e1.record()
-            e1.synchronize()
-            pk[name] = round(work / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
-        csrc = [torch.empty(128 << 20, dtype=torch.float32, device=dev).normal_() for _ in range(2)]   # 512 MiB each
-        cdst = [torch.empty(128 << 20, dtype=torch.float32, device=dev) for _ in range(2)]
-        B.fpq_probe_peak(B.FPQ_PROBE_COPY, 1, csrc[0], cdst[0])
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        work = sum(B.fpq_probe_peak(B.FPQ_PROBE_COPY, 1, csrc[i & 1], cdst[i & 1]) for i in range(8))
-        e1.record()
-        e1.synchronize()
-        pk["copy_GB/s_read_plus_write"] = round(work / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
-        del csrc, cdst
-        pk["note"] = ("register-only MFMA loops with operands that change every instruction, and a 512 MiB device copy; "
-                      "the nominal peaks are %g / %g TFLOP/s and %g GB/s" % (PEAK_BF16_TFLOPS, PEAK_FP8_TFLOPS, PEAK_HBM_GBS))
-        roofline["measured_peak"] = pk
-        roofline["frac_of_measured_peak"] = round(achieved / pk["bf16_mfma_TFLOP/s" if acc == B.FPQ_ACC_FP32 else "fp8_mfma_TFLOP/s"], 4)
+        roofline["measured_peak"] = measure_peaks()
+        roofline["frac_of_measured_peak"] = round(achieved / roofline["measured_peak"][
+            "bf16_mfma_TFLOP/s" if acc == B.FPQ_ACC_FP32 else "fp8_mfma_TFLOP/s"], 4)
         # structured-sparse weight operand (2 of every 4 input channels kept): the configuration-4 convolution and a
         # 1280-wide linear layer, E2M1 weights, layer kernel alone on prepared codes, next to the dense call on the same
         # shape; TFLOP/s count the dense layer's 2MNK
