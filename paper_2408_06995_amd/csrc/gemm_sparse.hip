@@ -351,28 +351,46 @@ __global__ __launch_bounds__(256) void gemm_sparse_kernel(const GemmArgs a, cons
 
     // ---- epilogue: register r of a lane is weight row n = 8 (r / 4) + 4 g + r % 4 of block i, the lane is activation row m
     const float sxa = (a.sx_dev ? a.sx_dev[0] : a.sx) * a.alpha;
-    const int hw = CONV ? a.Ho * a.Wo : 1;
+    if constexpr (CONV) {
+        // NCHW: the lanes run along the pixel index, which is contiguous in y
+        const int hw = a.Ho * a.Wo;
 #pragma unroll
-    for (int j = 0; j < NI; ++j) {
-        const int m = m0 + wq * TQ + 32 * j + l32;
-        if (m >= a.M) continue;
-        float* ybase;
-        size_t nstride;
-        if (CONV) {
+        for (int j = 0; j < NI; ++j) {
+            const int m = m0 + wq * TQ + 32 * j + l32;
+            if (m >= a.M) continue;
             const int bi = m / hw;
-            ybase = a.y + (size_t)bi * a.N * hw + (m - bi * hw);
-            nstride = (size_t)hw;
-        } else {
-            ybase = a.y + (size_t)m * a.N;
-            nstride = 1;
+            float* ybase = a.y + (size_t)bi * a.N * hw + (m - bi * hw);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int n = n0 + wp * TP + 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
+                    if (n < a.N) ybase[(size_t)n * hw] = acc[i][j][r] * (sxa * a.sw[n]) + (a.bias ? a.bias[n] : 0.0f);
+                }
         }
+    } else {
+        // row-major [M, N]: the lanes hold rows, so each 32 x 32 block crosses a wavefront-private LDS tile (the K loop
+        // ended with a barrier; the ring is free) and leaves with 32 lanes on 128 consecutive bytes of a row
+        float* tile = reinterpret_cast<float*>(smem) + wave * (32 * 33);
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+        for (int i = 0; i < MI; ++i) {
+            const int nb = n0 + wp * TP + 32 * i;            // first column of the block
+            const int n = nb + l32;
+            const float sc = n < a.N ? sxa * a.sw[n] : 0.0f;
+            const float bv = (n < a.N && a.bias) ? a.bias[n] : 0.0f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int n = n0 + wp * TP + 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
-                if (n < a.N) ybase[(size_t)n * nstride] = acc[i][j][r] * (sxa * a.sw[n]) + (a.bias ? a.bias[n] : 0.0f);
+            for (int j = 0; j < NI; ++j) {
+                const int mb = m0 + wq * TQ + 32 * j;         // first row of the block
+#pragma unroll
+                for (int r = 0; r < 16; ++r) tile[l32 * 33 + 8 * (r >> 2) + 4 * g + (r & 3)] = acc[i][j][r];
+#pragma unroll
+                for (int rr = 0; rr < 16; ++rr) {
+                    const int ml = 2 * rr + g;
+                    const float v = tile[ml * 33 + l32];
+                    if (mb + ml < a.M && n < a.N) a.y[(size_t)(mb + ml) * a.N + n] = v * sc + bv;
+                }
             }
+        }
     }
 }
 
