@@ -352,7 +352,9 @@ def main():
         """What the part sustains on the bare matrix instructions and on a plain copy (probe kernels of the library)."""
         pk = {}
         pdst = torch.empty(2048 * 256, dtype=torch.float32, device=dev)
-        for name, kind, iters in (("bf16_mfma_TFLOP/s", B.FPQ_PROBE_MFMA_BF16, 1500), ("fp8_mfma_TFLOP/s", B.FPQ_PROBE_MFMA_FP8, 1500)):
+        for name, kind, iters in (("bf16_mfma_TFLOP/s", B.FPQ_PROBE_MFMA_BF16, 1500), ("fp8_mfma_TFLOP/s", B.FPQ_PROBE_MFMA_FP8, 1500),
+                                  ("bf16_mfma_with_conversions_64x160_TFLOP/s", B.FPQ_PROBE_MFMA_DECODE_64, 4000),
+                                  ("bf16_mfma_with_conversions_32x160_TFLOP/s", B.FPQ_PROBE_MFMA_DECODE_32, 8000)):
             B.fpq_probe_peak(kind, 100, None, pdst)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
@@ -369,8 +371,16 @@ def main():
         e1.record()
         e1.synchronize()
         pk["copy_GB/s_read_plus_write"] = round(work / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+        B.fpq_probe_peak(B.FPQ_PROBE_FILL, 1, None, cdst[0])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        work = sum(B.fpq_probe_peak(B.FPQ_PROBE_FILL, 1, None, cdst[i & 1]) for i in range(8))
+        e1.record()
+        e1.synchronize()
+        pk["fill_GB/s_write_only"] = round(work / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
         del csrc, cdst
-        pk["note"] = ("register-only MFMA loops with operands that change every instruction, and a 512 MiB device copy; "
+        pk["note"] = ("register-only MFMA loops with operands that change every instruction (bare, and with the code-to-bf16 "
+                      "conversions a k-step of the layer kernels' wave tiles pays), a 512 MiB device copy and a 512 MiB fill; "
                       "the nominal peaks are %g / %g TFLOP/s and %g GB/s" % (PEAK_BF16_TFLOPS, PEAK_FP8_TFLOPS, PEAK_HBM_GBS))
         return pk
 
@@ -385,10 +395,14 @@ def main():
         mp = measure_peaks()
         m_fl = mp["bf16_mfma_TFLOP/s" if acc == B.FPQ_ACC_FP32 else "fp8_mfma_TFLOP/s"] * 1e12
         m_bw = mp["copy_GB/s_read_plus_write"] * 1e9
+        m_fill = mp["fill_GB/s_write_only"] * 1e9
+        m_cvt = mp["bf16_mfma_with_conversions_64x160_TFLOP/s"]
         lines.append("# per shape class of %s, accumulate mode %s: layer kernel alone on prepared codes" % (args.workload, args.acc))
         lines.append("# t_min = max(2MNK / %.0f TFLOP/s, (activation codes + packed weights + fp32 output) / 8 TB/s): the published peaks" % (peak_fl / 1e12))
-        lines.append("# %%machine = the same with what this part sustained in this run on the bare matrix instruction (%.0f TFLOP/s) and "
-                     "on a device copy (%.0f GB/s read + write)" % (m_fl / 1e12, m_bw / 1e9))
+        lines.append("# %%machine = the same with what this part sustained in this run: 2MNK on the bare matrix instruction (%.0f TFLOP/s; "
+                     "%.0f with the conversions of a 64 x 160 wave tile in the loop), the fp32 output at the rate of a device fill "
+                     "(%.0f GB/s) plus codes and weights at that of a device copy (%.0f GB/s read + write)"
+                     % (m_fl / 1e12, m_cvt, m_fill / 1e9, m_bw / 1e9))
         lines.append("%-4s %-6s %1s %1s %6s %6s %6s %4s %9s %9s %7s %9s %6s %9s" % (
             "w", "kind", "k", "s", "M", "K", "N", "x", "us", "TFLOP/s", "%peak", "%roofline", "bound", "%machine"))
         tot_t, tot_min, tot_mach = 0.0, 0.0, 0.0
@@ -423,7 +437,7 @@ def main():
                 nbytes = buf.numel() + s.packed[tag].numel() + 4 * L.M * L.N
                 t_f, t_b = fl / peak_fl * 1e6, nbytes / (PEAK_HBM_GBS * 1e9) * 1e6
                 t_min = max(t_f, t_b)
-                t_mach = max(fl / m_fl * 1e6, nbytes / m_bw * 1e6)
+                t_mach = max(fl / m_fl * 1e6, (4 * L.M * L.N / m_fill + (nbytes - 4 * L.M * L.N) / m_bw) * 1e6)
                 lines.append("%-4s %-6s %1d %1d %6d %6d %6d %4d %9.1f %9.1f %7.1f %9.1f %6s %9.1f" % (
                     tag, L.kind, key[1], key[2], L.M, L.K, L.N, cnt, us, fl / us / 1e6, 100 * fl / (us * 1e-6) / peak_fl,
                     100 * t_min / us, "mfma" if t_f >= t_b else "hbm", 100 * t_mach / us))

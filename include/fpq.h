@@ -436,10 +436,19 @@ int fpq_gemm_grouped(const fpq_gemm_problem_t *problems, int count, int x_is_fp3
  *   FPQ_PROBE_MFMA_BF16  register-only loop of the bf16 matrix instruction of the fp32-accumulate mode, operands
  *                        that change with every instruction; dst receives 2048 * 256 floats (bytes = size of dst);
  *   FPQ_PROBE_MFMA_FP8   the same with the 8-bit matrix instruction of FPQ_ACC_FP8_MFMA;
- *   FPQ_PROBE_COPY       dst[0 .. bytes) = src[0 .. bytes), 16-byte aligned.
- * One launch on stream; work_out (host) receives the flops (MFMA kinds) or the bytes read plus written (copy) of
+ *   FPQ_PROBE_COPY       dst[0 .. bytes) = src[0 .. bytes), 16-byte aligned;
+ *   FPQ_PROBE_MFMA_DECODE_64 / _32
+ *                        the bf16 matrix instruction together with the code-to-bf16 conversions that the
+ *                        fp32-accumulate mode pays per k-step of a wave tile of 64 x 160 / 32 x 160 outputs (the two
+ *                        large-tile layer kernels), codes in registers: the ceiling of that instruction mix; dst as
+ *                        for FPQ_PROBE_MFMA_BF16;
+ *   FPQ_PROBE_FILL       dst[0 .. bytes) = a constant pattern, 16-byte aligned; src is not used.
+ * One launch on stream; work_out (host) receives the flops (MFMA kinds) or the bytes read plus written (copy, fill) of
  * that launch, for the caller to divide by the time it measures. */
-typedef enum fpq_probe_kind { FPQ_PROBE_MFMA_BF16 = 0, FPQ_PROBE_MFMA_FP8 = 1, FPQ_PROBE_COPY = 2 } fpq_probe_kind;
+typedef enum fpq_probe_kind {
+    FPQ_PROBE_MFMA_BF16 = 0, FPQ_PROBE_MFMA_FP8 = 1, FPQ_PROBE_COPY = 2, FPQ_PROBE_MFMA_DECODE_64 = 3, FPQ_PROBE_MFMA_DECODE_32 = 4,
+    FPQ_PROBE_FILL = 5
+} fpq_probe_kind;
 int fpq_probe_peak(int kind, int iterations, const void *src, void *dst, size_t bytes, double *work_out,
                    void *stream);
 

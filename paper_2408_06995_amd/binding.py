@@ -402,7 +402,7 @@ def fpq_int_gemm(xcodes, sx, zx, px_dev, packed_w, wbits, sw, zw, bias, y, M, N,
                               _stream()), "fpq_int_gemm")
 
 
-FPQ_PROBE_MFMA_BF16, FPQ_PROBE_MFMA_FP8, FPQ_PROBE_COPY = 0, 1, 2
+FPQ_PROBE_MFMA_BF16, FPQ_PROBE_MFMA_FP8, FPQ_PROBE_COPY, FPQ_PROBE_MFMA_DECODE_64, FPQ_PROBE_MFMA_DECODE_32, FPQ_PROBE_FILL = 0, 1, 2, 3, 4, 5
 
 
 def fpq_probe_peak(kind, iterations, src, dst):

@@ -931,10 +931,11 @@ int fpq_int_gemm(const uint8_t* xcodes, float sx, int32_t zx, const fpq_int_para
 
 int fpq_probe_peak(int kind, int iterations, const void* src, void* dst, size_t bytes, double* work_out, void* stream)
 {
-    if (kind < FPQ_PROBE_MFMA_BF16 || kind > FPQ_PROBE_COPY) return FPQ_ERR_UNSUPPORTED;
+    if (kind < FPQ_PROBE_MFMA_BF16 || kind > FPQ_PROBE_FILL) return FPQ_ERR_UNSUPPORTED;
     if (!dst || !work_out) return FPQ_ERR_NULL;
-    if (kind == FPQ_PROBE_COPY) {
-        if (!src) return FPQ_ERR_NULL;
+    const bool memory = kind == FPQ_PROBE_COPY || kind == FPQ_PROBE_FILL;
+    if (memory) {
+        if (kind == FPQ_PROBE_COPY && !src) return FPQ_ERR_NULL;
         if (bytes < 16 || ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15)) return FPQ_ERR_ALIGN;
     } else {
         if (iterations < 1 || iterations > (1 << 20)) return FPQ_ERR_SHAPE;
@@ -943,9 +944,11 @@ int fpq_probe_peak(int kind, int iterations, const void* src, void* dst, size_t 
     int grid = 0;
     const int st = launch_probe(kind, iterations, src, dst, bytes, &grid, static_cast<hipStream_t>(stream));
     if (st) return st;
-    if (kind == FPQ_PROBE_COPY)
-        *work_out = 2.0 * (double)(bytes / 16 * 16);                                  // bytes read + written
-    else                                                                              // flops: 32 MFMAs per iteration and wave
+    if (memory)                                                                        // bytes read + written
+        *work_out = (kind == FPQ_PROBE_COPY ? 2.0 : 1.0) * (double)(bytes / 16 * 16);
+    else if (kind == FPQ_PROBE_MFMA_DECODE_64 || kind == FPQ_PROBE_MFMA_DECODE_32)       // 10 or 5 MFMAs per iteration and wave
+        *work_out = (double)grid * 4.0 * iterations * (kind == FPQ_PROBE_MFMA_DECODE_64 ? 10.0 : 5.0) * 2.0 * 32 * 32 * 16;
+    else                                                                               // flops: 32 MFMAs per iteration and wave
         *work_out = (double)grid * 4.0 * iterations * 32.0 * 2.0 * 32 * 32 * (kind == FPQ_PROBE_MFMA_BF16 ? 16 : 64);
     return FPQ_OK;
 }

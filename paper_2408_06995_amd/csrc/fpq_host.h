@@ -261,7 +261,8 @@ int launch_int_pack_weights(const float* w, int64_t N, int64_t K, int bits, uint
 int launch_int_gemm(const uint8_t* x, float sx, int zx, const fpq_int_params* px_dev, const uint8_t* wrows, const int32_t* wsum,
                     int wbits, const float* sw, const int32_t* zw, const float* bias, float* y, int64_t M, int64_t N, int64_t K,
                     int32_t* xsum, hipStream_t st);
-// Machine-ceiling probes (peaks.hip): kind 0 / 1 = register-only bf16 / 8-bit MFMA loop, 2 = device copy.
+// Machine-ceiling probes (peaks.hip): kind 0 / 1 = register-only bf16 / 8-bit MFMA loop, 2 = device copy,
+// 3 / 4 = bf16 MFMA with the conversions of a 64 x 160 / 32 x 160 wave tile, 5 = device fill.
 int launch_probe(int kind, int iters, const void* src, void* dst, size_t bytes, int* grid_out, hipStream_t st);
 bool gemm_dma_applicable(const GemmArgs& a);
 int launch_gemm_dma(const GemmArgs& a, hipStream_t st);
