@@ -456,6 +456,60 @@ def main():
         sec_s = timed(acc, max(2, args.steps // 2), 1, static_scale=True)
         out["static_scale_step"] = {"ms_per_step": round(sec_s * 1e3, 4), "value": round(flops_step / sec_s / 1e12, 3),
                                     "unit": "TFLOP/s"}
+        # every layer from codes to codes: activation codes in, the result quantized in the epilogue for a following
+        # quantized layer (E4M3, per-tensor scale found beforehand from the layer's own fp32 result) and written as one
+        # byte per output.  One launch per layer and a quarter of the output bytes: what a chain of quantized layers
+        # costs once scales are static, against the fp32-out launches of the roofline object.
+        def codes_to_codes():
+            yq = torch.empty(max(s.L.M * ((s.L.N + 15) // 16 * 16) for s in states), dtype=torch.uint8, device=dev)
+            sy = {}
+            ymax = torch.empty(2, dtype=torch.float32, device=dev)
+            for s in states:          # calibrate the output scales (untimed): absmax of the layer's fp32 result
+                L = s.L
+                buf = codes_bufs[L.name]
+                if buf is None:
+                    continue
+                for tag, fw in (("w8", FW8), ("w4", FW4)):
+                    if L.kind == "conv":
+                        B.fpq_conv2d(buf, 0, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, y, L.B, L.Cin, L.H,
+                                     L.W, L.Cout, L.k, L.k, L.stride, L.pad, acc, part_buf)
+                    else:
+                        B.fpq_gemm(buf, 0, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, y, L.M, L.N, L.K, acc,
+                                   part_buf)
+                    sy[L.name, tag] = torch.empty(2, dtype=torch.float32, device=dev)
+                    B.fpq_absmax(y[:L.M * L.N], FX[3], sy[L.name, tag][0:1], sy[L.name, tag][1:2], amax_ws)
+
+            def run():
+                for tag, fw in (("w8", FW8), ("w4", FW4)):
+                    for s in states:
+                        L = s.L
+                        buf = codes_bufs[L.name]
+                        if buf is None:
+                            continue
+                        if L.kind == "conv":
+                            B.fpq_conv2d_codes_out(buf, 0, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, FX, 0.0,
+                                                   sy[L.name, tag][1:2], yq, L.B, L.Cin, L.H, L.W, L.Cout, L.k, L.k, L.stride,
+                                                   L.pad, acc, part_buf)
+                        else:
+                            B.fpq_gemm_codes_out(buf, 0, FX, 0.0, s.scale[1:2], s.packed[tag], fw, s.sw[tag], None, FX, 0.0,
+                                                 sy[L.name, tag][1:2], yq, L.M, L.N, L.K, acc, part_buf)
+            run()
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                run()
+            graph.replay()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(3):
+                graph.replay()
+            e1.record()
+            e1.synchronize()
+            return e0.elapsed_time(e1) / 3
+        c_ms = codes_to_codes()
+        out["codes_to_codes_step"] = {"ms_per_step": round(c_ms, 4), "value": round(g_fl / (c_ms * 1e-3) / 1e12, 2),
+                                      "unit": "TFLOP/s", "frac_of_bf16_peak": round(g_fl / (c_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                                      "note": "all layers, codes in, E4M3 codes out with static scales, one launch per layer"}
         # the other accumulate mode, same step
         other = B.FPQ_ACC_FP8_MFMA if acc == B.FPQ_ACC_FP32 else B.FPQ_ACC_FP32
         sec_o = timed(other, max(2, args.steps // 2), 1)
