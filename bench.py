@@ -34,8 +34,8 @@ SEARCH_OPS = 11                        # vector instructions per element and can
 # split-K reductions included): not measurable from inside this script, hence a constant, valid only for the workload,
 # accumulate mode and call structure it was taken on; the summary file named here holds the command and the arithmetic.
 MEASURED_TRAFFIC = {
-    ("cfg5", "fp32", "grouped"): {"bytes_per_launch": 65.01e6,
-                                  "source": "profiles/cfg5_layer_kernels_hbm_traffic_pmc.txt: 30.36 MB fetched + 34.65 MB written "
+    ("cfg5", "fp32", "grouped"): {"bytes_per_launch": 65.00e6,
+                                  "source": "profiles/cfg5_layer_kernels_hbm_traffic_pmc.txt: 30.35 MB fetched + 34.65 MB written "
                                             "per layer over 4 x 500 layers"},
 }
 
@@ -387,9 +387,9 @@ def main():
             e1.record()
             e1.synchronize()
             pk[name] = round(work / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
-            for _ in range(60):        # long enough for the power reading to settle, then read it with the probe still running
+            for _ in range(30):        # long enough for the power reading to settle, then read it with the probe still running
                 B.fpq_probe_peak(kind, iters, None, pdst)
-            time.sleep(0.3)
+            time.sleep(0.12)
             pk[name.replace("_TFLOP/s", "_board")] = board_state()
             torch.cuda.synchronize()
         csrc = [torch.empty(128 << 20, dtype=torch.float32, device=dev).normal_() for _ in range(2)]   # 512 MiB each
